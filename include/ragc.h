@@ -1,0 +1,176 @@
+/*
+ * ragc -- prefix-cached paged prefill attention for gfx950 (MI355X), C ABI.
+ *
+ * The hot path of knowledge caching for retrieval-augmented generation: the
+ * K/V tensors of retrieved documents are kept in fixed-size, non-contiguous
+ * blocks referenced from the nodes of a prefix tree over document ids
+ * (paper Sec. 5.1, knowledge tree); a request whose document sequence matches a
+ * path of the tree computes only its non-cached tokens and attends over the
+ * cached blocks (Sec. 3.2 "Full prefill computation"; Sec. 4 "prefix caching
+ * kernel"; Sec. 6: multi-head and grouped-query attention); the K/V of the new
+ * tokens is handed back for caching (Sec. 4); blocks move between GPU and host
+ * memory (Sec. 3.2 "Cache hit", Sec. 5.1 "Swap out only once").
+ *
+ * Conventions
+ *   - Stateless: the library allocates nothing and keeps nothing between calls.
+ *     Every buffer belongs to the caller.  Calls validate their arguments on the
+ *     host, enqueue work on the given HIP stream and return; completion is
+ *     observed through the stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Pointers are marked [device], [host] or [pinned host].
+ *   - Every entry point returns 0 or a negative ragc_status.  On error nothing has
+ *     been enqueued.  ragc_last_error() gives a thread-local message.
+ *   - Block size is 16 tokens.  head_dim is 64 or 128.  dtype is fp32 or bf16 and is
+ *     the type of the pool, of q/k_new/v_new and of the output.
+ *
+ * Pool layout.  Two planes, K and V, each
+ *       [num_blocks][kv_heads][16][head_dim]           (row-major)
+ *   with `block_stride_elems` elements between consecutive blocks of a plane
+ *   (>= kv_heads*16*head_dim).  One (block, kv head) tile is contiguous (4 KiB for
+ *   bf16 at head_dim 128); one block of a plane is contiguous (what swap moves).
+ *
+ * Addressing.  Logical position j of request r (0 <= j < prefix_len+new_len)
+ *   lives in block block_table[r][j / 16], slot j % 16.  Positions below
+ *   prefix_len[r] are the cached documents (read only); positions from
+ *   prefix_len[r] on are the request's new tokens (written by the append).
+ *
+ * Preconditions the library cannot check on the device side
+ *   - every block that receives new tokens belongs to that request alone (shared
+ *     chains cover only full blocks inside the prefix);
+ *   - block_table rows hold ceil((prefix_len+new_len)/16) valid block ids;
+ *   - no swap writes a block that a running attention call reads.
+ *   When host mirrors of the tables are passed they ARE checked.
+ */
+#ifndef RAGC_H
+#define RAGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RAGC_BLOCK_SIZE 16
+
+typedef enum ragc_status {
+    RAGC_OK = 0,
+    RAGC_ERR_NULL = -1,      /* a required pointer is NULL */
+    RAGC_ERR_SHAPE = -2,     /* unsupported or inconsistent shape / dtype / flag */
+    RAGC_ERR_RANGE = -3,     /* a length or block id is out of range */
+    RAGC_ERR_ALIGN = -4,     /* a pointer or stride is not 16-byte aligned */
+    RAGC_ERR_HIP = -5,       /* a HIP runtime call failed */
+    RAGC_ERR_WORKSPACE = -6  /* workspace missing or too small */
+} ragc_status;
+
+typedef enum ragc_dtype { RAGC_DTYPE_F32 = 0, RAGC_DTYPE_BF16 = 1 } ragc_dtype;
+
+/* Paged K/V pool of one layer. */
+typedef struct ragc_kv_pool {
+    void* k;                    /* [device] K plane */
+    void* v;                    /* [device] V plane */
+    int32_t num_blocks;
+    int32_t block_size;         /* must be 16 */
+    int32_t kv_heads;
+    int32_t head_dim;           /* 64 or 128 */
+    int32_t dtype;              /* ragc_dtype */
+    int32_t reserved;           /* must be 0 */
+    int64_t block_stride_elems; /* elements between blocks of one plane */
+} ragc_kv_pool;
+
+/* One batch of augmented requests.  The request's document sequence has already
+ * been matched against the tree by the caller: what arrives here is the block
+ * chain of the matched path (block_table), the cached length (prefix_len, the
+ * paper's alpha) and the non-cached length (new_len, the paper's beta).
+ * The h_* arrays are host copies of the same metadata: h_prefix_len, h_new_len
+ * are required (the launch is sized from them); h_block_table is optional and,
+ * when given, every entry the call will touch is range-checked. */
+typedef struct ragc_batch {
+    int32_t num_reqs;
+    int32_t table_stride;          /* entries per block_table row */
+    const int32_t* prefix_len;     /* [device] [num_reqs] */
+    const int32_t* new_len;        /* [device] [num_reqs] */
+    const int32_t* new_start;      /* [device] [num_reqs+1] exclusive scan of new_len */
+    const int32_t* block_table;    /* [device] [num_reqs][table_stride] */
+    const int32_t* h_prefix_len;   /* [host] [num_reqs] */
+    const int32_t* h_new_len;      /* [host] [num_reqs] */
+    const int32_t* h_block_table;  /* [host] optional */
+} ragc_batch;
+
+/* flags of ragc_prefill_attn */
+#define RAGC_ATTN_APPEND_FUSED 0x1u /* also write k_new/v_new into their paged slots */
+#define RAGC_ATTN_NO_SPLIT 0x2u     /* never split the key range across workgroups */
+
+/* flags of ragc_kv_swap */
+#define RAGC_SWAP_AUTO 0x0u
+#define RAGC_SWAP_MEMCPY 0x1u /* one hipMemcpyAsync per run of adjacent blocks and plane */
+#define RAGC_SWAP_KERNEL 0x2u /* copy kernel that reads/writes the pinned host pool directly */
+
+#define RAGC_SWAP_TO_DEVICE 0
+#define RAGC_SWAP_TO_HOST 1
+
+/* Library version, major*10000 + minor*100 + patch. */
+int ragc_version(void);
+
+/* Thread-local text of the last error on this thread ("" if none). */
+const char* ragc_last_error(void);
+
+/* Bytes of K/V cache one token occupies in a model: 2 * layers * kv_heads *
+ * head_dim * sizeof(dtype) (the KV Size column of the paper's model table).
+ * Returns 0 on bad arguments. */
+int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype);
+
+/* Workspace ragc_prefill_attn needs for this batch (bytes, possibly 0).  Only the
+ * host arrays of `batch` are read.  Returns a negative ragc_status on error. */
+int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads,
+                                    uint32_t flags);
+
+/* Prefill attention of the new tokens of every request over the cached paged
+ * prefix and their own fresh K/V, causal (Sec. 3.2, Sec. 4, Sec. 6):
+ *     out[t,h,:] = softmax_j( scale * q[t,h,:] . K_j ) V_j ,  j = 0 .. prefix_len+i
+ * where t = new_start[r]+i, kv head = h / (q_heads / kv_heads), K_j/V_j come from the
+ * pool for j < prefix_len[r] and from k_new/v_new (row new_start[r]+j-prefix_len[r])
+ * otherwise.  Softmax and accumulation are fp32; for bf16 the probabilities are
+ * rounded to bf16 before the PV product and the output is rounded to nearest even.
+ *   q, out        [device] [sum new_len][q_heads][head_dim]
+ *   k_new, v_new  [device] [sum new_len][kv_heads][head_dim]
+ *   workspace     [device] >= ragc_prefill_attn_workspace() bytes, 256-byte aligned
+ *                 (may be NULL when that is 0)
+ * With RAGC_ATTN_APPEND_FUSED the same pass performs ragc_kv_append; the pool then
+ * holds byte-identical contents to a separate ragc_kv_append call.
+ * Requests with new_len == 0 are skipped.  prefix_len == 0 is plain causal
+ * self-attention. */
+int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Write the fresh K/V of every request into its paged slots (Sec. 4: the tensors
+ * of the accessed documents are cached after the first token): row
+ * new_start[r]+i of k_new/v_new goes to position prefix_len[r]+i.  A byte copy. */
+int ragc_kv_append(const ragc_kv_pool* pool, const ragc_batch* batch, const void* k_new, const void* v_new,
+                   void* stream);
+
+/* Copy whole blocks (all kv heads, K and V planes) between the device pool and a
+ * pinned host pool of the same per-block layout (Sec. 5.1 "Swap out only once";
+ * Sec. 3.2 "Cache hit": the transfer is part of the hit latency).
+ *   host_k, host_v            [pinned host] planes [num_host_slots][kv_heads][16][head_dim]
+ *   host_block_stride_elems   elements between host slots of one plane
+ *   dev_block_ids, host_slots [host] n entries each; pair i moves device block
+ *                             dev_block_ids[i] <-> host slot host_slots[i]
+ *   direction                 RAGC_SWAP_TO_DEVICE or RAGC_SWAP_TO_HOST
+ * The id arrays are read before the call returns.  `stream` is normally a side
+ * stream; the caller orders it against attention with events.  A byte copy. */
+int ragc_kv_swap(const ragc_kv_pool* pool, void* host_k, void* host_v, int64_t host_block_stride_elems,
+                 int32_t num_host_slots, const int32_t* dev_block_ids, const int32_t* host_slots, int32_t n,
+                 int32_t direction, uint32_t flags, void* stream);
+
+/* Test helper: gather `length` logical positions of request `req` from the pool
+ * into contiguous [length][kv_heads][head_dim] buffers.  A byte copy.
+ *   k_out, v_out [device]; length <= table_stride*16 */
+int ragc_kv_gather(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t req, int32_t length, void* k_out,
+                   void* v_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RAGC_H */
