@@ -1,0 +1,277 @@
+// C-ABI front end: argument validation, error reporting and dispatch to the
+// gfx950 kernels.  Every check runs on the host before anything is enqueued.
+#include "../../include/ragc.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "ragc_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int esize_of(int32_t dtype) { return dtype == RAGC_DTYPE_BF16 ? 2 : dtype == RAGC_DTYPE_F32 ? 4 : 0; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_pool(const ragc_kv_pool* pool) {
+    if (!pool) return fail(RAGC_ERR_NULL, "pool is NULL");
+    if (!pool->k || !pool->v) return fail(RAGC_ERR_NULL, "pool->k / pool->v is NULL");
+    if (pool->block_size != RAGC_BLOCK_SIZE) return fail(RAGC_ERR_SHAPE, "block_size %d (must be 16)", pool->block_size);
+    if (pool->head_dim != 64 && pool->head_dim != 128) return fail(RAGC_ERR_SHAPE, "head_dim %d (must be 64 or 128)", pool->head_dim);
+    if (esize_of(pool->dtype) == 0) return fail(RAGC_ERR_SHAPE, "dtype %d unknown", pool->dtype);
+    if (pool->reserved != 0) return fail(RAGC_ERR_SHAPE, "pool->reserved must be 0");
+    if (pool->kv_heads <= 0 || pool->kv_heads > 65535) return fail(RAGC_ERR_SHAPE, "kv_heads %d", pool->kv_heads);
+    if (pool->num_blocks <= 0) return fail(RAGC_ERR_SHAPE, "num_blocks %d", pool->num_blocks);
+    const int64_t min_stride = (int64_t)pool->kv_heads * RAGC_BLOCK_SIZE * pool->head_dim;
+    if (pool->block_stride_elems < min_stride)
+        return fail(RAGC_ERR_SHAPE, "block_stride_elems %lld < kv_heads*16*head_dim = %lld", (long long)pool->block_stride_elems, (long long)min_stride);
+    if (!aligned16(pool->k) || !aligned16(pool->v) || (pool->block_stride_elems * esize_of(pool->dtype)) % 16 != 0)
+        return fail(RAGC_ERR_ALIGN, "pool planes and block stride must be 16-byte aligned");
+    return RAGC_OK;
+}
+
+struct BatchInfo {
+    int64_t total_new = 0;
+    int32_t max_new = 0;
+};
+
+// Host-side checks of the batch metadata.  need_device: the device arrays are required.
+int check_batch(const ragc_kv_pool* pool, const ragc_batch* b, bool need_device, BatchInfo* info) {
+    if (!b) return fail(RAGC_ERR_NULL, "batch is NULL");
+    if (b->num_reqs < 0 || b->num_reqs > 65535) return fail(RAGC_ERR_SHAPE, "num_reqs %d", b->num_reqs);
+    if (b->num_reqs == 0) return RAGC_OK;
+    if (!b->h_prefix_len || !b->h_new_len) return fail(RAGC_ERR_NULL, "h_prefix_len / h_new_len (host copies) are required");
+    if (need_device && (!b->prefix_len || !b->new_len || !b->new_start || !b->block_table))
+        return fail(RAGC_ERR_NULL, "a device array of the batch is NULL");
+    if (b->table_stride <= 0) return fail(RAGC_ERR_SHAPE, "table_stride %d", b->table_stride);
+    for (int r = 0; r < b->num_reqs; ++r) {
+        const int64_t p = b->h_prefix_len[r], n = b->h_new_len[r];
+        if (p < 0 || n < 0) return fail(RAGC_ERR_RANGE, "request %d: prefix_len %lld, new_len %lld", r, (long long)p, (long long)n);
+        const int64_t blocks = (p + n + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE;
+        if (blocks > b->table_stride)
+            return fail(RAGC_ERR_RANGE, "request %d: %lld tokens need %lld table entries, table_stride is %d", r, (long long)(p + n), (long long)blocks, b->table_stride);
+        if (b->h_block_table) {
+            const int32_t* row = b->h_block_table + (int64_t)r * b->table_stride;
+            for (int64_t i = 0; i < blocks; ++i)
+                if (row[i] < 0 || row[i] >= pool->num_blocks)
+                    return fail(RAGC_ERR_RANGE, "request %d: block_table[%lld] = %d outside [0, %d)", r, (long long)i, row[i], pool->num_blocks);
+        }
+        info->total_new += n;
+        info->max_new = std::max<int32_t>(info->max_new, (int32_t)n);
+    }
+    if (info->total_new > (int64_t)1 << 30) return fail(RAGC_ERR_RANGE, "sum of new_len %lld too large", (long long)info->total_new);
+    return RAGC_OK;
+}
+
+ragc::PagedBatch make_paged(const ragc_kv_pool* pool, const ragc_batch* b) {
+    ragc::PagedBatch pb;
+    pb.pool_k = pool->k;
+    pb.pool_v = pool->v;
+    pb.block_stride = pool->block_stride_elems;
+    pb.prefix_len = b->prefix_len;
+    pb.new_len = b->new_len;
+    pb.new_start = b->new_start;
+    pb.block_table = b->block_table;
+    pb.table_stride = b->table_stride;
+    pb.num_reqs = b->num_reqs;
+    pb.kv_heads = pool->kv_heads;
+    pb.head_dim = pool->head_dim;
+    return pb;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(RAGC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ragc_version(void) { return 100; }
+
+const char* ragc_last_error(void) { return g_err; }
+
+int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype) {
+    const int es = esize_of(dtype);
+    if (layers <= 0 || kv_heads <= 0 || head_dim <= 0 || es == 0) return 0;
+    return (int64_t)2 * layers * kv_heads * head_dim * es;
+}
+
+int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads, uint32_t flags) {
+    (void)flags;
+    g_err[0] = 0;
+    if (!pool) return fail(RAGC_ERR_NULL, "pool is NULL");
+    if (!batch) return fail(RAGC_ERR_NULL, "batch is NULL");
+    if (q_heads <= 0 || pool->kv_heads <= 0 || q_heads % pool->kv_heads != 0)
+        return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
+    return 0;
+}
+
+int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    if (flags & ~(RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT)) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
+    if (q_heads <= 0 || q_heads % pool->kv_heads != 0)
+        return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
+    if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
+        return fail(RAGC_ERR_SHAPE, "softmax_scale must be positive and finite");
+    BatchInfo info;
+    if (int rc = check_batch(pool, batch, true, &info)) return rc;
+    if (batch->num_reqs == 0 || info.total_new == 0) return RAGC_OK;
+    if (!q || !k_new || !v_new || !out) return fail(RAGC_ERR_NULL, "q / k_new / v_new / out is NULL");
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
+        return fail(RAGC_ERR_ALIGN, "q / k_new / v_new / out must be 16-byte aligned");
+
+    ragc::AttnLaunch a;
+    a.b = make_paged(pool, batch);
+    a.q = q;
+    a.k_new = k_new;
+    a.v_new = v_new;
+    a.out = out;
+    a.pool_k_w = pool->k;
+    a.pool_v_w = pool->v;
+    a.q_heads = q_heads;
+    a.group = q_heads / pool->kv_heads;
+    a.scale_log2e = softmax_scale * 1.44269504088896340736f;
+    a.fused_append = (flags & RAGC_ATTN_APPEND_FUSED) ? 1 : 0;
+    a.max_new = info.max_new;
+    a.total_new = (int32_t)info.total_new;
+    const hipError_t e = pool->dtype == RAGC_DTYPE_BF16 ? ragc::launch_attn_bf16(a, static_cast<hipStream_t>(stream))
+                                                        : ragc::launch_attn_f32(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
+    return RAGC_OK;
+}
+
+int ragc_kv_append(const ragc_kv_pool* pool, const ragc_batch* batch, const void* k_new, const void* v_new, void* stream) {
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    BatchInfo info;
+    if (int rc = check_batch(pool, batch, true, &info)) return rc;
+    if (batch->num_reqs == 0 || info.total_new == 0) return RAGC_OK;
+    if (!k_new || !v_new) return fail(RAGC_ERR_NULL, "k_new / v_new is NULL");
+    if (!aligned16(k_new) || !aligned16(v_new)) return fail(RAGC_ERR_ALIGN, "k_new / v_new must be 16-byte aligned");
+    const hipError_t e = ragc::launch_append(make_paged(pool, batch), pool->k, pool->v, k_new, v_new, (int32_t)info.total_new,
+                                             esize_of(pool->dtype), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "append launch");
+    return RAGC_OK;
+}
+
+int ragc_kv_gather(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t req, int32_t length, void* k_out,
+                   void* v_out, void* stream) {
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    if (!batch) return fail(RAGC_ERR_NULL, "batch is NULL");
+    if (!batch->block_table) return fail(RAGC_ERR_NULL, "block_table is NULL");
+    if (req < 0 || req >= batch->num_reqs) return fail(RAGC_ERR_RANGE, "req %d outside [0, %d)", req, batch->num_reqs);
+    if (length < 0 || (int64_t)length > (int64_t)batch->table_stride * RAGC_BLOCK_SIZE)
+        return fail(RAGC_ERR_RANGE, "length %d exceeds table capacity %lld", length, (long long)batch->table_stride * RAGC_BLOCK_SIZE);
+    if (batch->h_block_table) {
+        const int32_t* row = batch->h_block_table + (int64_t)req * batch->table_stride;
+        for (int i = 0; i < (length + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE; ++i)
+            if (row[i] < 0 || row[i] >= pool->num_blocks)
+                return fail(RAGC_ERR_RANGE, "block_table[%d] = %d outside [0, %d)", i, row[i], pool->num_blocks);
+    }
+    if (length == 0) return RAGC_OK;
+    if (!k_out || !v_out) return fail(RAGC_ERR_NULL, "k_out / v_out is NULL");
+    if (!aligned16(k_out) || !aligned16(v_out)) return fail(RAGC_ERR_ALIGN, "k_out / v_out must be 16-byte aligned");
+    const hipError_t e = ragc::launch_gather(make_paged(pool, batch), req, length, k_out, v_out, esize_of(pool->dtype),
+                                             static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "gather launch");
+    return RAGC_OK;
+}
+
+int ragc_kv_swap(const ragc_kv_pool* pool, void* host_k, void* host_v, int64_t host_block_stride_elems,
+                 int32_t num_host_slots, const int32_t* dev_block_ids, const int32_t* host_slots, int32_t n,
+                 int32_t direction, uint32_t flags, void* stream) {
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    if (!host_k || !host_v) return fail(RAGC_ERR_NULL, "host_k / host_v is NULL");
+    if (n < 0) return fail(RAGC_ERR_RANGE, "n %d", n);
+    if (direction != RAGC_SWAP_TO_DEVICE && direction != RAGC_SWAP_TO_HOST) return fail(RAGC_ERR_SHAPE, "direction %d", direction);
+    if (flags > RAGC_SWAP_KERNEL) return fail(RAGC_ERR_SHAPE, "unknown swap flags 0x%x", flags);
+    const int es = esize_of(pool->dtype);
+    const int64_t plane_elems = (int64_t)pool->kv_heads * RAGC_BLOCK_SIZE * pool->head_dim;
+    if (host_block_stride_elems < plane_elems)
+        return fail(RAGC_ERR_SHAPE, "host_block_stride_elems %lld < %lld", (long long)host_block_stride_elems, (long long)plane_elems);
+    if (!aligned16(host_k) || !aligned16(host_v) || (host_block_stride_elems * es) % 16 != 0)
+        return fail(RAGC_ERR_ALIGN, "host planes and stride must be 16-byte aligned");
+    if (num_host_slots <= 0) return fail(RAGC_ERR_SHAPE, "num_host_slots %d", num_host_slots);
+    if (n == 0) return RAGC_OK;
+    if (!dev_block_ids || !host_slots) return fail(RAGC_ERR_NULL, "dev_block_ids / host_slots is NULL");
+    for (int i = 0; i < n; ++i) {
+        if (dev_block_ids[i] < 0 || dev_block_ids[i] >= pool->num_blocks)
+            return fail(RAGC_ERR_RANGE, "dev_block_ids[%d] = %d outside [0, %d)", i, dev_block_ids[i], pool->num_blocks);
+        if (host_slots[i] < 0 || host_slots[i] >= num_host_slots)
+            return fail(RAGC_ERR_RANGE, "host_slots[%d] = %d outside [0, %d)", i, host_slots[i], num_host_slots);
+    }
+    {  // two pairs must not write the same destination
+        std::vector<int32_t> dst(direction == RAGC_SWAP_TO_DEVICE ? dev_block_ids : host_slots,
+                                 (direction == RAGC_SWAP_TO_DEVICE ? dev_block_ids : host_slots) + n);
+        std::sort(dst.begin(), dst.end());
+        if (std::adjacent_find(dst.begin(), dst.end()) != dst.end())
+            return fail(RAGC_ERR_RANGE, "two pairs write the same destination block");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t plane_bytes = plane_elems * es;
+    const int64_t dev_stride = pool->block_stride_elems * es;
+    const int64_t host_stride = host_block_stride_elems * es;
+    const bool to_dev = direction == RAGC_SWAP_TO_DEVICE;
+
+    if (flags == RAGC_SWAP_MEMCPY) {
+        // one copy per plane and run of pairs that are adjacent on both sides
+        const bool dense = dev_stride == plane_bytes && host_stride == plane_bytes;
+        int i = 0;
+        while (i < n) {
+            int j = i + 1;
+            while (dense && j < n && dev_block_ids[j] == dev_block_ids[j - 1] + 1 && host_slots[j] == host_slots[j - 1] + 1) ++j;
+            const size_t bytes = (size_t)(j - i) * plane_bytes;
+            for (int plane = 0; plane < 2; ++plane) {
+                char* d = static_cast<char*>(plane ? pool->v : pool->k) + (int64_t)dev_block_ids[i] * dev_stride;
+                char* h = static_cast<char*>(plane ? host_v : host_k) + (int64_t)host_slots[i] * host_stride;
+                const hipError_t e = to_dev ? hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s)
+                                            : hipMemcpyAsync(h, d, bytes, hipMemcpyDeviceToHost, s);
+                if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync");
+            }
+            i = j;
+        }
+        return RAGC_OK;
+    }
+
+    // copy kernel over the host-mapped pinned pool
+    void *hk_dev = nullptr, *hv_dev = nullptr;
+    hipError_t e = hipHostGetDevicePointer(&hk_dev, host_k, 0);
+    if (e != hipSuccess) return hip_fail(e, "host_k is not pinned, device-mapped memory (hipHostGetDevicePointer)");
+    e = hipHostGetDevicePointer(&hv_dev, host_v, 0);
+    if (e != hipSuccess) return hip_fail(e, "host_v is not pinned, device-mapped memory (hipHostGetDevicePointer)");
+    for (int i = 0; i < n; i += ragc::kSwapPairsPerLaunch) {
+        const int cnt = std::min(ragc::kSwapPairsPerLaunch, n - i);
+        ragc::SwapPairs pairs{};
+        std::memcpy(pairs.dev, dev_block_ids + i, sizeof(int32_t) * cnt);
+        std::memcpy(pairs.slot, host_slots + i, sizeof(int32_t) * cnt);
+        e = ragc::launch_swap(static_cast<char*>(pool->k), static_cast<char*>(pool->v), dev_stride,
+                              static_cast<char*>(hk_dev), static_cast<char*>(hv_dev), host_stride, plane_bytes, pairs, cnt,
+                              to_dev ? 1 : 0, s);
+        if (e != hipSuccess) return hip_fail(e, "swap kernel launch");
+    }
+    return RAGC_OK;
+}
+
+}  // extern "C"

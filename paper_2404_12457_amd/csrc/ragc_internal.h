@@ -1,0 +1,61 @@
+// Internal launch interface between the C-ABI front end (ragc_api.cpp) and the
+// gfx950 kernels.  Not installed; the public contract is include/ragc.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ragc {
+
+constexpr int kBlock = 16;  // tokens per paged block
+
+// Everything a device kernel needs to find the K/V of a batch.
+struct PagedBatch {
+    const void* pool_k;
+    const void* pool_v;
+    int64_t block_stride;  // elements between blocks of one plane
+    const int32_t* prefix_len;
+    const int32_t* new_len;
+    const int32_t* new_start;
+    const int32_t* block_table;
+    int32_t table_stride;
+    int32_t num_reqs;
+    int32_t kv_heads;
+    int32_t head_dim;
+};
+
+struct AttnLaunch {
+    PagedBatch b;
+    const void* q;
+    const void* k_new;
+    const void* v_new;
+    void* out;
+    void* pool_k_w;  // writable aliases of the pool planes (fused append)
+    void* pool_v_w;
+    int32_t q_heads;
+    int32_t group;      // q_heads / kv_heads
+    float scale_log2e;  // softmax_scale * log2(e)
+    int32_t fused_append;
+    int32_t max_new;  // max over requests of new_len (host-side)
+    int32_t total_new;
+};
+
+hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
+hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
+
+hipError_t launch_append(const PagedBatch& b, void* pool_k, void* pool_v, const void* k_new, const void* v_new,
+                         int32_t total_new, int esize, hipStream_t s);
+hipError_t launch_gather(const PagedBatch& b, int32_t req, int32_t length, void* k_out, void* v_out, int esize,
+                         hipStream_t s);
+
+// Block copies between the device pool and a host-mapped pinned pool.  Pairs are
+// passed by value in the kernel argument buffer, so no device staging is needed.
+constexpr int kSwapPairsPerLaunch = 384;
+struct SwapPairs {
+    int32_t dev[kSwapPairsPerLaunch];
+    int32_t slot[kSwapPairsPerLaunch];
+};
+hipError_t launch_swap(char* dev_k, char* dev_v, int64_t dev_block_bytes_stride, char* host_k, char* host_v,
+                       int64_t host_block_bytes_stride, int64_t plane_block_bytes, const SwapPairs& pairs, int32_t n,
+                       int to_device, hipStream_t s);
+
+}  // namespace ragc

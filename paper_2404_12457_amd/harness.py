@@ -1,0 +1,105 @@
+"""Device-side plumbing shared by the GPU tests, the smoke check and the
+benchmark: allocate a pool with PyTorch-ROCm, place a generated workload in it,
+build the C structs.  Allocation and copies only -- no arithmetic of the method.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workload import Workload
+
+
+def torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Storage array (uint16 bf16 bits / float32) -> device tensor of that dtype."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> storage array (uint16 bits for bf16, float32 otherwise)."""
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.contiguous().cpu().numpy()
+
+
+class DeviceWorkload:
+    """A Workload resident on the GPU: pool planes (poison everywhere except the
+    cached blocks), Q / fresh K,V, tables, and the ragc structs pointing at them."""
+
+    def __init__(self, w: Workload, device="cuda", resident_host_blocks: bool = True, with_host_table: bool = True):
+        self.w = w
+        self.device = device
+        td = torch_dtype(w.dtype)
+        self.pool_k = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
+        self.pool_v = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
+        ids = w.used_block_ids
+        uk, uv = w.used_k, w.used_v
+        if not resident_host_blocks and w.host_dev_blocks.size:
+            keep = ~np.isin(ids, w.host_dev_blocks)
+            ids, uk, uv = ids[keep], uk[keep], uv[keep]
+        if ids.size:
+            idx = torch.from_numpy(ids.astype(np.int64)).to(device)
+            self.pool_k[idx] = to_device(uk, w.dtype, device)
+            self.pool_v[idx] = to_device(uv, w.dtype, device)
+        self.q = to_device(w.q, w.dtype, device)
+        self.k_new = to_device(w.k_new, w.dtype, device)
+        self.v_new = to_device(w.v_new, w.dtype, device)
+        self.out = torch.full(tuple(w.q.shape), float("nan"), dtype=td, device=device)
+        self.h_prefix_len = np.ascontiguousarray(w.prefix_len, np.int32)
+        self.h_new_len = np.ascontiguousarray(w.new_len, np.int32)
+        self.h_block_table = np.ascontiguousarray(w.block_table, np.int32) if with_host_table else None
+        self.d_prefix_len = torch.from_numpy(self.h_prefix_len).to(device)
+        self.d_new_len = torch.from_numpy(self.h_new_len).to(device)
+        self.d_new_start = torch.from_numpy(np.ascontiguousarray(w.new_start, np.int32)).to(device)
+        self.d_block_table = torch.from_numpy(np.ascontiguousarray(w.block_table, np.int32)).to(device)
+        self.dtype_code = B.RAGC_DTYPE_BF16 if w.dtype == "bf16" else B.RAGC_DTYPE_F32
+        self.pool = B.make_pool(self.pool_k, self.pool_v, w.num_blocks, w.kv_heads, w.head_dim, self.dtype_code)
+        self.batch = B.make_batch(w.num_reqs, w.table_stride, self.d_prefix_len, self.d_new_len, self.d_new_start,
+                                  self.d_block_table, self.h_prefix_len, self.h_new_len, self.h_block_table)
+        self.workspace = None
+        self.workspace_bytes = 0
+        # host tier
+        self.host_k = self.host_v = None
+        if w.host_dev_blocks.size:
+            shp = (w.num_host_slots, w.kv_heads, 16, w.head_dim)
+            self.host_k = torch.zeros(shp, dtype=td).pin_memory()
+            self.host_v = torch.zeros(shp, dtype=td).pin_memory()
+            where = {int(b): i for i, b in enumerate(w.used_block_ids)}
+            sel = np.asarray([where[int(b)] for b in w.host_dev_blocks])
+            slots = torch.from_numpy(w.host_slots.astype(np.int64))
+            self.host_k[slots] = to_device(w.used_k[sel], w.dtype, "cpu")
+            self.host_v[slots] = to_device(w.used_v[sel], w.dtype, "cpu")
+
+    def ensure_workspace(self, flags: int = 0):
+        need = B.ragc_prefill_attn_workspace(self.pool, self.batch, self.w.q_heads, flags)
+        if need > self.workspace_bytes:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self.workspace_bytes = need
+
+    def attn(self, flags: int = 0, stream: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        self.ensure_workspace(flags)
+        out = self.out if out is None else out
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        B.ragc_prefill_attn(self.pool, self.batch, self.q, self.k_new, self.v_new, out, self.w.q_heads,
+                            self.w.softmax_scale, flags, self.workspace, self.workspace_bytes, s)
+        return out
+
+    def append(self, stream: Optional[int] = None):
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        B.ragc_kv_append(self.pool, self.batch, self.k_new, self.v_new, s)
+
+    def swap(self, dev_blocks: np.ndarray, host_slots: np.ndarray, direction: int, flags: int = 0,
+             stream: Optional[int] = None):
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        w = self.w
+        B.ragc_kv_swap(self.pool, self.host_k, self.host_v, w.kv_heads * 16 * w.head_dim, w.num_host_slots, dev_blocks,
+                       host_slots, direction, flags, s)

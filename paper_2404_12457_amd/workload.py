@@ -261,6 +261,7 @@ def build_workload(
     q_gain: float = 1.0,
     host_fraction: float = 0.0,
     table_stride: Optional[int] = None,
+    placement_seed: Optional[int] = None,
 ) -> Workload:
     """Draw tensors and place the cached prefix into paged blocks.
 
@@ -301,7 +302,7 @@ def build_workload(
                 assert w._node_kv[key][0].shape[0] == length, "same path, different length"
 
     # block assignment
-    perm = _gen(seed, _T_PERM).permutation(num_blocks).astype(np.int32)
+    perm = _gen(seed if placement_seed is None else placement_seed, _T_PERM).permutation(num_blocks).astype(np.int32)
     nxt = 0
     max_blocks = max([1] + [(int(p) + int(n) + BLOCK - 1) // BLOCK for p, n in zip(w.prefix_len, w.new_len)])
     w.table_stride = int(table_stride) if table_stride is not None else max_blocks
@@ -488,20 +489,26 @@ def make_small(
     q_gain: float = 1.0,
     shared_first_doc: int = 0,
     table_stride: Optional[int] = None,
+    placement_seed: Optional[int] = None,
+    docs: Optional[List[List[Tuple[int, int]]]] = None,
 ) -> Workload:
     """Ad-hoc case for tests: `lens` is a list of (prefix_len, new_len); every
     request gets one private cached document of prefix_len tokens, optionally
-    preceded by a common first document of `shared_first_doc` tokens."""
+    preceded by a common first document of `shared_first_doc` tokens; `docs` gives
+    the document sequences explicitly instead."""
     reqs = []
     for i, (p, n) in enumerate(lens):
-        docs: List[Tuple[int, int]] = []
-        if shared_first_doc and p > shared_first_doc:
-            docs.append((1, shared_first_doc))
-            docs.append((100 + i, p - shared_first_doc))
+        docs_i: List[Tuple[int, int]] = []
+        if docs is not None:
+            docs_i = list(docs[i])
+            assert sum(l for _, l in docs_i) == p
+        elif shared_first_doc and p > shared_first_doc:
+            docs_i.append((1, shared_first_doc))
+            docs_i.append((100 + i, p - shared_first_doc))
         elif p > 0:
-            docs.append((100 + i, p))
-        reqs.append(RequestSpec(docs, n, 0))
+            docs_i.append((100 + i, p))
+        reqs.append(RequestSpec(docs_i, n, 0))
     need = 2 + sum((p + n + BLOCK - 1) // BLOCK for p, n in lens)
     nb = num_blocks if num_blocks is not None else max(8, 2 * need)
     return build_workload(f"small-{dtype}-{q_heads}/{kv_heads}-d{head_dim}", dtype, q_heads, kv_heads, head_dim,
-                          nb, reqs, seed, sigma, q_gain, table_stride=table_stride)
+                          nb, reqs, seed, sigma, q_gain, table_stride=table_stride, placement_seed=placement_seed)

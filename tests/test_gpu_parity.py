@@ -1,0 +1,302 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Floating point within 2e-2 (bf16) / 1e-4 (fp32) max abs
+error plus a relative-L2 gate; gather / append / swap compared byte for byte."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import attention as OA
+from oracle import paged as OP
+from paper_2404_12457_amd import binding as B
+from paper_2404_12457_amd import workload as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = {"bf16": 1e-2, "f32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2404_12457_amd import harness
+
+    B.load()
+    return harness
+
+
+def _bits(t):
+    """Integer view of a tensor so NaN poison compares equal to itself."""
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+
+
+def _check_all(H, w, flags=0):
+    dw = H.DeviceWorkload(w)
+    out = dw.attn(flags)
+    torch.cuda.synchronize()
+    got = U.out_to_f64(H.to_host(out), w.dtype)
+    want = U.oracle_all(w)
+    assert np.all(np.isfinite(got)), "non-finite output"
+    err = float(np.max(np.abs(got - want))) if want.size else 0.0
+    assert err <= U.TOL[w.dtype], f"{w.name}: max abs err {err}"
+    if want.size:
+        assert U.rel_l2(got, want) <= REL_L2[w.dtype], f"{w.name}: rel L2 {U.rel_l2(got, want)}"
+    return dw, got, want
+
+
+SMALL = [
+    # dtype, Hq, Hkv, D, [(prefix, new)...], q_gain
+    ("f32", 8, 2, 128, [(0, 1), (5, 3), (100, 70), (33, 0), (64, 16)], 1.0),
+    ("f32", 4, 4, 64, [(17, 40), (0, 33)], 4.0),
+    ("bf16", 8, 2, 128, [(0, 17), (37, 20), (64, 1), (100, 133), (15, 0), (300, 250)], 1.0),
+    ("bf16", 4, 4, 128, [(1, 1), (16, 16), (63, 65), (64, 64), (65, 63)], 1.0),
+    ("bf16", 4, 1, 64, [(70, 90), (0, 5), (129, 31)], 1.0),
+    ("bf16", 16, 2, 128, [(130, 40), (0, 200)], 1.0),
+    ("bf16", 6, 2, 128, [(50, 45), (7, 100)], 1.0),  # group of 3: rows of a token straddle tiles
+    ("bf16", 8, 2, 128, [(200, 130), (31, 2)], 8.0),  # sharp softmax
+    ("bf16", 32, 32, 128, [(96, 100)], 1.0),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: f"{c[0]}-{c[1]}/{c[2]}-d{c[3]}-g{c[5]}")
+@pytest.mark.parametrize("fused", [0, 1], ids=["plain", "fused"])
+def test_small_cases_match_oracle(H, case, fused):
+    dtype, hq, hkv, d, lens, gain = case
+    w = W.make_small(dtype, hq, hkv, d, lens, seed=1000 + len(lens) * 7 + hq, q_gain=gain)
+    _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED if fused else 0)
+
+
+def test_config1_fp32(H):
+    _check_all(H, W.make_config(1))
+    _check_all(H, W.make_config(1, peaked=True))
+
+
+def test_config2_full_size_all_rows(H):
+    _check_all(H, W.make_config(2), B.RAGC_ATTN_APPEND_FUSED)
+
+
+@pytest.mark.parametrize("index,peaked", [(2, True), (3, False), (3, True), (4, False), (4, True)])
+def test_full_size_configs_sampled_rows(H, index, peaked):
+    w = W.make_config(index, peaked=peaked)
+    dw = H.DeviceWorkload(w)
+    out = dw.attn(B.RAGC_ATTN_APPEND_FUSED)
+    torch.cuda.synchronize()
+    got_all = U.out_to_f64(H.to_host(out), w.dtype)
+    assert np.all(np.isfinite(got_all))
+    worst, num, den = 0.0, 0.0, 0.0
+    for r in range(w.num_reqs):
+        rows = U.sample_rows(w, r, 48, seed=index)
+        want = U.oracle_rows(w, r, rows)
+        s0 = int(w.new_start[r])
+        got = np.stack([got_all[s0 + i, h] for i, h in rows])
+        worst = max(worst, float(np.max(np.abs(got - want))))
+        num += float(np.sum((got - want) ** 2))
+        den += float(np.sum(want**2))
+    assert worst <= U.TOL[w.dtype], f"{w.name}: max abs err {worst}"
+    assert (num / den) ** 0.5 <= REL_L2[w.dtype]
+
+
+def test_single_key_returns_v_bit_exact(H):
+    w = W.make_small("bf16", 4, 2, 128, [(0, 1)], seed=5)
+    dw = H.DeviceWorkload(w)
+    out = H.to_host(dw.attn())
+    for h in range(4):
+        assert np.array_equal(out[0, h], w.v_new[0, h // 2])
+    w = W.make_small("f32", 4, 2, 64, [(0, 1)], seed=6)
+    out = H.to_host(H.DeviceWorkload(w).attn())
+    for h in range(4):
+        assert np.array_equal(out[0, h], w.v_new[0, h // 2])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_output_is_invariant_under_block_placement(H, dtype):
+    lens = [(100, 37), (64, 64), (0, 20)]
+    a = W.make_small(dtype, 8, 2, 128, lens, seed=21, placement_seed=1)
+    b = W.make_small(dtype, 8, 2, 128, lens, seed=21, placement_seed=2, num_blocks=200)
+    assert not np.array_equal(a.block_table[:, :4], b.block_table[:, :4])
+    oa = H.to_host(H.DeviceWorkload(a).attn())
+    ob = H.to_host(H.DeviceWorkload(b).attn())
+    assert np.array_equal(oa, ob)
+
+
+def test_requests_do_not_depend_on_batch_composition(H):
+    w = W.make_small("bf16", 8, 2, 128, [(80, 30), (200, 150), (17, 64)], seed=31)
+    dw = H.DeviceWorkload(w)
+    full = H.to_host(dw.attn()).copy()
+    for r in range(w.num_reqs):
+        s = w.new_slice(r)
+        hp, hn = dw.h_prefix_len[r : r + 1].copy(), dw.h_new_len[r : r + 1].copy()
+        ns = torch.tensor([0, int(hn[0])], dtype=torch.int32, device="cuda")
+        batch = B.make_batch(1, w.table_stride, dw.d_prefix_len[r : r + 1], dw.d_new_len[r : r + 1], ns,
+                             dw.d_block_table[r], hp, hn, dw.h_block_table[r])
+        out = torch.zeros_like(dw.q[s])
+        B.ragc_prefill_attn(dw.pool, batch, dw.q[s], dw.k_new[s], dw.v_new[s], out, w.q_heads, w.softmax_scale, 0,
+                            None, 0, torch.cuda.current_stream().cuda_stream)
+        assert np.array_equal(H.to_host(out), full[s])
+
+
+def test_requests_sharing_a_block_chain_and_query_agree(H):
+    docs = [[(1, 64)], [(1, 64)]]
+    w = W.make_small("bf16", 8, 2, 128, [(64, 20), (64, 20)], seed=41, docs=docs)
+    assert np.array_equal(w.block_table[0, :4], w.block_table[1, :4])  # one physical chain
+    assert w.block_table[0, 4] != w.block_table[1, 4]
+    dw = H.DeviceWorkload(w)
+    for t in (dw.q, dw.k_new, dw.v_new):
+        t[20:40] = t[0:20]
+    out = H.to_host(dw.attn(B.RAGC_ATTN_APPEND_FUSED))
+    assert np.array_equal(out[:20], out[20:40])
+
+
+def test_future_tokens_do_not_change_a_row(H):
+    w = W.make_small("bf16", 4, 2, 128, [(40, 100)], seed=51)
+    dw = H.DeviceWorkload(w)
+    base = H.to_host(dw.attn()).copy()
+    dw.k_new[60:] += 3.0
+    dw.v_new[60:] -= 2.0
+    pert = H.to_host(dw.attn())
+    assert np.array_equal(pert[:60], base[:60]) and not np.array_equal(pert[60:], base[60:])
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 8, 2, 128), ("f32", 4, 4, 64), ("bf16", 4, 4, 64)])
+def test_append_fused_standalone_and_oracle_agree_bytewise(H, dtype, hq, hkv, d):
+    lens = [(0, 5), (37, 20), (64, 1), (100, 133), (15, 0), (250, 47)]
+    w = W.make_small(dtype, hq, hkv, d, lens, seed=61)
+    pk, pv = w.pool_image()
+    OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
+    a = H.DeviceWorkload(w)
+    a.append()
+    b = H.DeviceWorkload(w)
+    b.attn(B.RAGC_ATTN_APPEND_FUSED)
+    torch.cuda.synchronize()
+    want_k, want_v = H.to_device(pk, dtype), H.to_device(pv, dtype)
+    for dw in (a, b):
+        assert torch.equal(_bits(dw.pool_k), _bits(want_k))
+        assert torch.equal(_bits(dw.pool_v), _bits(want_v))
+
+
+def test_gather_is_the_logical_sequence(H):
+    w = W.make_small("bf16", 8, 2, 128, [(37, 20), (100, 133), (0, 9)], seed=71)
+    dw = H.DeviceWorkload(w)
+    dw.append()
+    for r in range(w.num_reqs):
+        kf, vf = w.full_kv(r)
+        L = kf.shape[0]
+        ko = torch.zeros((L, w.kv_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+        vo = torch.zeros_like(ko)
+        B.ragc_kv_gather(dw.pool, dw.batch, r, L, ko, vo, torch.cuda.current_stream().cuda_stream)
+        assert np.array_equal(H.to_host(ko), kf) and np.array_equal(H.to_host(vo), vf)
+
+
+def test_followup_request_reads_appended_blocks(H):
+    """After the append a later request with a longer cached prefix over the same
+    blocks must equal full recomputation over everything."""
+    w = W.make_small("bf16", 8, 2, 128, [(37, 20)], seed=81)
+    dw = H.DeviceWorkload(w)
+    dw.attn(B.RAGC_ATTN_APPEND_FUSED)
+    P2, N2 = 57, 7
+    g = np.random.Generator(np.random.Philox(key=[81, 99]))
+    q2 = W.f32_to_bf16_bits(g.standard_normal((N2, 8, 128), dtype=np.float32))
+    k2 = W.f32_to_bf16_bits(g.standard_normal((N2, 2, 128), dtype=np.float32))
+    v2 = W.f32_to_bf16_bits(g.standard_normal((N2, 2, 128), dtype=np.float32))
+    hp, hn = np.array([P2], np.int32), np.array([N2], np.int32)
+    dp, dn = torch.tensor(hp, device="cuda"), torch.tensor(hn, device="cuda")
+    ds = torch.tensor([0, N2], dtype=torch.int32, device="cuda")
+    batch = B.make_batch(1, w.table_stride, dp, dn, ds, dw.d_block_table, hp, hn, dw.h_block_table)
+    dq, dk, dv = (H.to_device(x, "bf16") for x in (q2, k2, v2))
+    out = torch.zeros_like(dq)
+    B.ragc_prefill_attn(dw.pool, batch, dq, dk, dv, out, 8, w.softmax_scale, 0, None, 0,
+                        torch.cuda.current_stream().cuda_stream)
+    kf, vf = w.full_kv(0)
+    kall = np.concatenate([kf, k2]), np.concatenate([vf, v2])
+    want = OA.prefill_attn(W.to_f64(q2, "bf16"), W.to_f64(kall[0], "bf16"), W.to_f64(kall[1], "bf16"), P2, w.softmax_scale)
+    got = W.to_f64(H.to_host(out), "bf16")
+    assert np.max(np.abs(got - want)) <= 2e-2 and U.rel_l2(got, want) <= 1e-2
+
+
+def test_chunked_prefill_equals_single_call(H):
+    """An uncached document appended first, the question afterwards (second call's
+    prefix grown by the document) must give the question rows of the single call."""
+    w = W.make_small("bf16", 8, 2, 128, [(70, 48 + 25)], seed=91, table_stride=12)
+    one = H.DeviceWorkload(w)
+    ref = H.to_host(one.attn(B.RAGC_ATTN_APPEND_FUSED)).copy()
+    two = H.DeviceWorkload(w)
+    st = torch.cuda.current_stream().cuda_stream
+    out = torch.zeros_like(two.q)
+    for (p, lo, hi) in ((70, 0, 48), (118, 48, 73)):
+        hp, hn = np.array([p], np.int32), np.array([hi - lo], np.int32)
+        dp, dn = torch.tensor(hp, device="cuda"), torch.tensor(hn, device="cuda")
+        ds = torch.tensor([0, hi - lo], dtype=torch.int32, device="cuda")
+        batch = B.make_batch(1, w.table_stride, dp, dn, ds, two.d_block_table, hp, hn, two.h_block_table)
+        B.ragc_prefill_attn(two.pool, batch, two.q[lo:hi], two.k_new[lo:hi], two.v_new[lo:hi], out[lo:hi], 8,
+                            w.softmax_scale, B.RAGC_ATTN_APPEND_FUSED, None, 0, st)
+        torch.cuda.synchronize()
+    got = W.to_f64(H.to_host(out), "bf16")
+    want = U.oracle_all(w)
+    assert np.max(np.abs(got - want)) <= 2e-2
+    # same kernel, same tiles of keys in the same order for the document rows: identical bits there
+    assert np.array_equal(H.to_host(out)[:48], ref[:48])
+    assert torch.equal(_bits(one.pool_k), _bits(two.pool_k)) and torch.equal(_bits(one.pool_v), _bits(two.pool_v))
+
+
+@pytest.mark.parametrize("mode", [B.RAGC_SWAP_KERNEL, B.RAGC_SWAP_MEMCPY, B.RAGC_SWAP_AUTO])
+def test_swap_round_trip_and_attention_after_swap_in(H, mode):
+    reqs = [W.RequestSpec([(1, 100), (2, 60)], 30), W.RequestSpec([(1, 100), (3, 200)], 17), W.RequestSpec([(4, 50)], 9)]
+    w = W.build_workload("swap-small", "bf16", 8, 2, 128, 128, reqs, seed=101, host_fraction=0.4)
+    assert w.host_dev_blocks.size > 0
+    full = H.DeviceWorkload(w)  # everything resident: the reference output
+    ref = H.to_host(full.attn()).copy()
+    part = H.DeviceWorkload(w, resident_host_blocks=False)  # host-resident blocks are poison on the device
+    part.swap(w.host_dev_blocks, w.host_slots, B.RAGC_SWAP_TO_DEVICE, mode)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(part.pool_k), _bits(full.pool_k)) and torch.equal(_bits(part.pool_v), _bits(full.pool_v))
+    assert np.array_equal(H.to_host(part.attn()), ref)
+    # swap out into fresh slots, wipe the device copies, swap back in
+    part.host_k.zero_()
+    part.host_v.zero_()
+    rev = w.host_slots[::-1].copy()
+    part.swap(w.host_dev_blocks, rev, B.RAGC_SWAP_TO_HOST, mode)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(w.host_dev_blocks.astype(np.int64)).cuda()
+    part.pool_k[idx] = float("nan")
+    part.pool_v[idx] = float("nan")
+    part.swap(w.host_dev_blocks, rev, B.RAGC_SWAP_TO_DEVICE, mode)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(part.pool_k), _bits(full.pool_k)) and torch.equal(_bits(part.pool_v), _bits(full.pool_v))
+    assert np.array_equal(H.to_host(part.attn()), ref)
+
+
+def test_swap_on_a_side_stream_overlaps_and_orders_with_events(H):
+    w = W.make_config(5)
+    dw = H.DeviceWorkload(w, resident_host_blocks=False)
+    full = H.DeviceWorkload(w)
+    side = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    with torch.cuda.stream(side):
+        dw.swap(w.host_dev_blocks, w.host_slots, B.RAGC_SWAP_TO_DEVICE, 0, stream=side.cuda_stream)
+        done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    out = dw.attn()
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(dw.pool_k), _bits(full.pool_k))
+    assert torch.equal(_bits(out), _bits(full.attn()))
+    got = U.out_to_f64(H.to_host(out), "bf16")
+    worst = 0.0
+    for r in (0, 5, 17, 31):
+        rows = U.sample_rows(w, r, 24, seed=5)
+        want = U.oracle_rows(w, r, rows)
+        s0 = int(w.new_start[r])
+        worst = max(worst, float(np.max(np.abs(np.stack([got[s0 + i, h] for i, h in rows]) - want))))
+    assert worst <= 2e-2
+
+
+def test_empty_batches_are_no_ops(H):
+    w = W.make_small("bf16", 4, 2, 128, [(20, 0), (0, 0)], seed=111)
+    dw = H.DeviceWorkload(w)
+    before = _bits(dw.pool_k).clone()
+    dw.attn(B.RAGC_ATTN_APPEND_FUSED)
+    dw.append()
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(dw.pool_k), before)
