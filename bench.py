@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-cached paged prefill path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2] [--no-extras]
+
+One step = one pass of the hot path over one batch of synthetic RAG-shaped input:
+ragc_prefill_attn with the fused K/V append (block-table gather, QK^T, causal mask,
+online softmax, PV, GQA grouping, new-token part, append, normalise + store).  The
+headline workload is configuration 2 (LLaMA2-7B-shaped layer, batch 8, 1024-token
+cached prefix, 100 new tokens).  Inputs are resident in HBM before the timed region;
+several pool copies are rotated so that consecutive steps do not hit the same lines
+of the 256 MB last-level cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+PCIE5_X16_GBS = 63.0
+
+
+def _time_steps(fn, steps, warmup, torch):
+    """Wall clock and HIP-event time of `steps` calls on the current stream."""
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def _rotating(w, copies, harness):
+    return [harness.DeviceWorkload(w) for _ in range(copies)]
+
+
+def bench_attention(w, steps, warmup, torch, harness, B, flags, copies=4):
+    dws = _rotating(w, copies, harness)
+    for d in dws:
+        d.ensure_workspace(flags)
+    wall_ms, ev_ms = _time_steps(lambda i: dws[i % copies].attn(flags), steps, warmup, torch)
+    del dws
+    torch.cuda.empty_cache()
+    return wall_ms, ev_ms
+
+
+def attn_bytes(w, fused):
+    return w.attn_min_bytes() + (w.append_bytes() // 2 if fused else 0)  # fused append adds only the writes
+
+
+def cpu_baseline(w, target_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the
+    workload: whole requests, cycling through the batch until the time target."""
+    from oracle import attention as OA
+    from paper_2404_12457_amd import workload as W
+
+    threads = OA.max_threads()
+    flops_done, t_used, reqs, toks = 0.0, 0.0, 0, 0
+    live = [r for r in range(w.num_reqs) if int(w.new_len[r]) > 0]
+    for it in range(100000):
+        r = live[it % len(live)]
+        n, p = int(w.new_len[r]), int(w.prefix_len[r])
+        kf, vf = w.full_kv(r)
+        s = w.new_slice(r)
+        q, k, v = W.to_f64(w.q[s], w.dtype), W.to_f64(kf, w.dtype), W.to_f64(vf, w.dtype)
+        t0 = time.perf_counter()
+        OA.prefill_attn(q, k, v, p, w.softmax_scale, threads=threads)
+        t_used += time.perf_counter() - t0
+        flops_done += 4.0 * w.head_dim * w.q_heads * (n * p + n * (n + 1) // 2)
+        reqs += 1
+        toks += n
+        if t_used > target_s:
+            break
+    return {"value": flops_done / t_used / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reqs} request passes (cycling the {len(live)} requests of {w.name}), all rows, fp64, {t_used:.1f} s",
+            "new_tokens_per_s": float(toks / t_used)}
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, help="configuration index for the headline line (2, 3 or 4)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other configurations, append and swap figures")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; the path issues no collective and --gpus > 1 is not supported")
+
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2404_12457_amd import binding as B
+    from paper_2404_12457_amd import harness
+    from paper_2404_12457_amd import workload as W
+
+    B.load()  # fails loudly if libragc.so is missing
+    FUSED = B.RAGC_ATTN_APPEND_FUSED
+    w = W.make_config(args.workload)
+    wall_ms, ev_ms = bench_attention(w, args.steps, args.warmup, torch, harness, B, FUSED)
+    flops, nbytes = w.attn_flops(), attn_bytes(w, True)
+    tflops = flops / (wall_ms * 1e-3) / 1e12
+    ach_gbs = nbytes / (ev_ms * 1e-3) / 1e9
+    ach_tfl = flops / (ev_ms * 1e-3) / 1e12
+    hbm_bound = (nbytes / (HBM_PEAK_GBS * 1e9)) > (flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": ach_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach_gbs / HBM_PEAK_GBS}
+    else:
+        roof = {"bound": "mfma", "achieved": ach_tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach_tfl / MFMA_BF16_PEAK_TFLOPS}
+    roof.update({"kernel": "attn_bf16_kernel<128>", "kernel_ms": ev_ms, "algorithmic_bytes": nbytes, "flops": flops,
+                 "mfma_frac": ach_tfl / MFMA_BF16_PEAK_TFLOPS, "hbm_frac": ach_gbs / HBM_PEAK_GBS,
+                 "traffic": read_traffic(f"attn_bf16_C{args.workload}")})
+
+    result = {
+        "metric": "prefix-cached prefill attention TFLOP/s + new-tokens/s; % of MFMA peak",
+        "value": tflops, "unit": "TFLOP/s", "new_tokens_per_s": w.total_new / (wall_ms * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "requests": w.num_reqs, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
+                   "head_dim": w.head_dim, "prefix_tokens": int(w.prefix_len.sum()), "new_tokens": w.total_new,
+                   "block_size": 16, "pool_blocks": w.num_blocks, "fused_append": True, "pool_copies_rotated": 4},
+        "roofline": roof,
+    }
+
+    if not args.no_extras:
+        extras = {}
+        steps2, warm2 = max(20, args.steps // 4), max(5, args.warmup // 2)
+        for idx in (1, 3, 4):
+            if idx == args.workload:
+                continue
+            wx = W.make_config(idx)
+            wm, em = bench_attention(wx, steps2, warm2, torch, harness, B, FUSED, copies=4 if idx != 1 else 1)
+            fl, by = wx.attn_flops(), attn_bytes(wx, True)
+            extras[f"C{idx}"] = {"workload": wx.name, "ms_per_step": wm, "kernel_ms": em, "tflops": fl / em / 1e9,
+                                 "new_tokens_per_s": wx.total_new / (wm * 1e-3), "mfma_frac": fl / em / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                                 "hbm_gbs": by / em / 1e6, "hbm_frac": by / em / 1e6 / HBM_PEAK_GBS}
+        # standalone append: at the workload's size and on a scaled sweep of the same row shape
+        dw = harness.DeviceWorkload(w)
+        _, em = _time_steps(lambda i: dw.append(), steps2, warm2, torch)
+        extras["append_C2"] = {"bytes": w.append_bytes(), "kernel_ms": em, "gbs": w.append_bytes() / em / 1e6,
+                               "hbm_frac": w.append_bytes() / em / 1e6 / HBM_PEAK_GBS}
+        del dw
+        big = W.build_workload("append-sweep", "bf16", 8, 8, 128, 1 << 17,
+                               [W.RequestSpec([], 65536) for _ in range(16)], seed=7)
+        dwb = harness.DeviceWorkload(big)
+        _, em = _time_steps(lambda i: dwb.append(), 20, 3, torch)
+        extras["append_sweep"] = {"bytes": big.append_bytes(), "kernel_ms": em, "gbs": big.append_bytes() / em / 1e6,
+                                  "hbm_frac": big.append_bytes() / em / 1e6 / HBM_PEAK_GBS}
+        del dwb, big
+        torch.cuda.empty_cache()
+        # host tier: swap-in of the host-resident blocks of configuration 5, both mechanisms
+        w5 = W.make_config(5)
+        d5 = harness.DeviceWorkload(w5, resident_host_blocks=False)
+        sw_bytes = int(w5.host_dev_blocks.size) * 2 * w5.kv_heads * 16 * w5.head_dim * 2
+        side = torch.cuda.Stream()
+        for name, mode in (("kernel", B.RAGC_SWAP_KERNEL), ("memcpy", B.RAGC_SWAP_MEMCPY)):
+            with torch.cuda.stream(side):
+                _, em = _time_steps(lambda i: d5.swap(w5.host_dev_blocks, w5.host_slots, B.RAGC_SWAP_TO_DEVICE, mode,
+                                                      stream=side.cuda_stream), 10, 2, torch)
+            extras[f"swap_in_{name}"] = {"blocks": int(w5.host_dev_blocks.size), "bytes": sw_bytes, "ms": em,
+                                         "gbs": sw_bytes / em / 1e6, "pcie5_x16_frac": sw_bytes / em / 1e6 / PCIE5_X16_GBS}
+        with torch.cuda.stream(side):
+            _, em = _time_steps(lambda i: d5.swap(w5.host_dev_blocks, w5.host_slots, B.RAGC_SWAP_TO_HOST, B.RAGC_SWAP_KERNEL,
+                                                  stream=side.cuda_stream), 10, 2, torch)
+        extras["swap_out_kernel"] = {"bytes": sw_bytes, "ms": em, "gbs": sw_bytes / em / 1e6,
+                                     "pcie5_x16_frac": sw_bytes / em / 1e6 / PCIE5_X16_GBS}
+        # whole batch resident; then the real flow: swap-in on the side stream while the
+        # requests that are already resident run, the others wait on the event
+        _, em_alone = _time_steps(lambda i: d5.attn(FUSED), 20, 3, torch)
+        res_idx = [r for r in range(w5.num_reqs) if not w5.needs_swap[r]]
+        swp_idx = [r for r in range(w5.num_reqs) if w5.needs_swap[r]]
+        b_res, keep1 = d5.sub_batch(res_idx)
+        b_swp, keep2 = d5.sub_batch(swp_idx)
+        ev = torch.cuda.Event()
+
+        def serial(i):
+            d5.swap(w5.host_dev_blocks, w5.host_slots, B.RAGC_SWAP_TO_DEVICE, 0)
+            d5.attn(FUSED)
+
+        def overlapped(i):
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                d5.swap(w5.host_dev_blocks, w5.host_slots, B.RAGC_SWAP_TO_DEVICE, 0, stream=side.cuda_stream)
+                ev.record(side)
+            d5.attn_batch(b_res, FUSED)
+            torch.cuda.current_stream().wait_event(ev)
+            d5.attn_batch(b_swp, FUSED)
+
+        _, em_ser = _time_steps(serial, 10, 2, torch)
+        _, em_ovl = _time_steps(overlapped, 10, 2, torch)
+        side.synchronize()
+        extras["C5"] = {"workload": w5.name, "requests_resident": len(res_idx), "requests_waiting_for_swap": len(swp_idx),
+                        "attn_ms_all_resident": em_alone, "swap_then_attn_ms": em_ser, "swap_overlapped_with_attn_ms": em_ovl,
+                        "tflops_all_resident": w5.attn_flops() / em_alone / 1e9,
+                        "mfma_frac_all_resident": w5.attn_flops() / em_alone / 1e9 / MFMA_BF16_PEAK_TFLOPS}
+        del d5
+        result["other_workloads"] = extras
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

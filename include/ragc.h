@@ -82,6 +82,11 @@ typedef struct ragc_kv_pool {
  * been matched against the tree by the caller: what arrives here is the block
  * chain of the matched path (block_table), the cached length (prefix_len, the
  * paper's alpha) and the non-cached length (new_len, the paper's beta).
+ * new_start[r] is the row of q/k_new/v_new/out where request r's new tokens
+ * begin; its rows are contiguous.  Normally the exclusive scan of new_len
+ * starting at 0.  ragc_prefill_attn accepts any offsets (so a subset of a batch
+ * can be launched over the same packed tensors); ragc_kv_append needs
+ * new_start[r+1] = new_start[r] + new_len[r] (new_start[0] may be non-zero).
  * The h_* arrays are host copies of the same metadata: h_prefix_len, h_new_len
  * are required (the launch is sized from them); h_block_table is optional and,
  * when given, every entry the call will touch is range-checked. */
@@ -90,7 +95,7 @@ typedef struct ragc_batch {
     int32_t table_stride;          /* entries per block_table row */
     const int32_t* prefix_len;     /* [device] [num_reqs] */
     const int32_t* new_len;        /* [device] [num_reqs] */
-    const int32_t* new_start;      /* [device] [num_reqs+1] exclusive scan of new_len */
+    const int32_t* new_start;      /* [device] [num_reqs+1] first packed row of each request */
     const int32_t* block_table;    /* [device] [num_reqs][table_stride] */
     const int32_t* h_prefix_len;   /* [host] [num_reqs] */
     const int32_t* h_new_len;      /* [host] [num_reqs] */

@@ -11,7 +11,8 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// Request that owns packed new-token index t: largest r with new_start[r] <= t.
+// Request that owns packed row t: largest r with new_start[r] <= t (new_start is
+// increasing and new_start[0] <= t < new_start[num_reqs]).
 __device__ __forceinline__ int find_request(const int32_t* __restrict__ new_start, int num_reqs, int t) {
     int lo = 0, hi = num_reqs;  // invariant: new_start[lo] <= t < new_start[hi]
     while (hi - lo > 1) {
@@ -30,16 +31,18 @@ __global__ __launch_bounds__(256) void append_kernel(PagedBatch b, char* __restr
     const int chunks_per_head = head_bytes >> 4;
     const int chunks_per_row = b.kv_heads * chunks_per_head;
     const long long total = (long long)total_new * chunks_per_row;
+    const int first_row = b.new_start[0];  // a sub-batch may start anywhere in the packed arrays
     for (long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x; c < total; c += (long long)gridDim.x * blockDim.x) {
-        const int t = (int)(c / chunks_per_row);
-        const int in_row = (int)(c - (long long)t * chunks_per_row);
+        const int t_rel = (int)(c / chunks_per_row);
+        const int in_row = (int)(c - (long long)t_rel * chunks_per_row);
+        const int t = first_row + t_rel;
         const int g = in_row / chunks_per_head;
         const int ch = in_row - g * chunks_per_head;
         const int r = find_request(b.new_start, b.num_reqs, t);
         const int pos = b.prefix_len[r] + (t - b.new_start[r]);
         const int blk = b.block_table[(long long)r * b.table_stride + (pos >> 4)];
         const long long dst = ((long long)blk * b.block_stride + ((long long)g * kBlock + (pos & 15)) * b.head_dim) * esize + (ch << 4);
-        const long long src = (long long)c << 4;
+        const long long src = ((long long)first_row * chunks_per_row + c) << 4;
         const u32x4 kk = *reinterpret_cast<const u32x4*>(k_new + src);
         const u32x4 vv = *reinterpret_cast<const u32x4*>(v_new + src);
         *reinterpret_cast<u32x4*>(pool_k + dst) = kk;

@@ -79,6 +79,24 @@ class DeviceWorkload:
             self.host_k[slots] = to_device(w.used_k[sel], w.dtype, "cpu")
             self.host_v[slots] = to_device(w.used_v[sel], w.dtype, "cpu")
 
+    def sub_batch(self, reqs):
+        """A batch struct over a subset of the requests, addressing the same packed
+        tensors.  Returns (struct, keepalive)."""
+        idx = np.asarray(reqs, np.int64)
+        w = self.w
+        hp = np.ascontiguousarray(w.prefix_len[idx], np.int32)
+        hn = np.ascontiguousarray(w.new_len[idx], np.int32)
+        hs = np.ascontiguousarray(np.concatenate([w.new_start[idx], [0]]), np.int32)
+        ht = np.ascontiguousarray(w.block_table[idx], np.int32)
+        dev = [torch.from_numpy(a).to(self.device) for a in (hp, hn, hs, ht)]
+        batch = B.make_batch(len(idx), w.table_stride, dev[0], dev[1], dev[2], dev[3], hp, hn, ht)
+        return batch, (hp, hn, hs, ht, dev)
+
+    def attn_batch(self, batch, flags: int = 0, stream: Optional[int] = None):
+        s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        B.ragc_prefill_attn(self.pool, batch, self.q, self.k_new, self.v_new, self.out, self.w.q_heads,
+                            self.w.softmax_scale, flags, self.workspace, self.workspace_bytes, s)
+
     def ensure_workspace(self, flags: int = 0):
         need = B.ragc_prefill_attn_workspace(self.pool, self.batch, self.w.q_heads, flags)
         if need > self.workspace_bytes:

@@ -363,26 +363,20 @@ def build_workload(
         marked: set = set()
         order = _gen(seed, _T_HOST).permutation(R)
         target = host_fraction * U
-        depth_from_leaf = 0
-        max_depth = max(len(rq.docs) for rq in requests)
 
         def count_marked() -> int:
             return sum(1 for b in used_ids if _is_marked(block_nodes[b], marked))
 
-        done = False
-        while not done and depth_from_leaf < max_depth:
-            for ri in order:
-                docs = [d for d, _ in requests[ri].docs]
-                if len(docs) - depth_from_leaf < 1:
-                    continue
-                # keep the first document of every path on the GPU when it has one
-                if len(docs) - depth_from_leaf == 1 and len(docs) > 1:
-                    continue
-                marked.add(tuple(docs[: len(docs) - depth_from_leaf]))
-                if count_marked() >= target:
-                    done = True
-                    break
-            depth_from_leaf += 1
+        # request by request (random order): everything below the first document goes to
+        # the host (a lone document goes whole), until the target share is reached; cold
+        # paths are evicted as a whole while hot ones stay resident
+        for ri in order:
+            docs = [d for d, _ in requests[ri].docs]
+            if not docs:
+                continue
+            marked.add(tuple(docs[:2]) if len(docs) > 1 else tuple(docs))
+            if count_marked() >= target:
+                break
         host_blocks = [b for b in used_ids if _is_marked(block_nodes[b], marked)]
         S = len(host_blocks)
         w.num_host_slots = max(1, int(np.ceil(S * 1.25)))
