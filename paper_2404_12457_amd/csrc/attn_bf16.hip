@@ -7,10 +7,20 @@
 // request tokens are computed), and the same pass can store that fresh K/V into its
 // paged slots (Sec. 4: tensors are cached after the first token).
 //
-// Mapping.  One workgroup = (request, kv head, 128 rows); a row is a (new token,
+// Mapping.  One work item = (request, kv head, 128 rows); a row is a (new token,
 // q head of the group) pair, token-major, so the G q heads of a GQA group share
-// every K/V tile and a tile's causal frontier stays narrow.  4 waves x 32 rows.
-// Keys stream through LDS in tiles of 64 (four pool blocks).
+// every K/V tile and a tile's causal frontier stays narrow.  A wave owns 32 rows.
+// Keys stream through LDS in tiles of 64 (four pool blocks): each wave copies one
+// 16-token block of K and of V per tile straight from HBM into LDS
+// (global_load_lds, 16 bytes per lane), one tile ahead of the math, into a ring of
+// stages.  Rows are stored unpadded with their 16-byte chunks XOR-swizzled so that
+// both the 16-byte K reads and the transposing V reads are bank-conflict free.
+//
+// NG wave groups of 4 waves work on the same 128 rows but on alternating key tiles
+// (each with its own online-softmax state, merged through LDS at the end), so that a
+// launch with few work items still puts 8 waves on a CU and one group's softmax
+// overlaps the other's MFMAs.  With many work items NG = 1 and two workgroups share
+// a CU instead.
 //
 // The products are computed transposed so that a lane owns ONE query row:
 //   S^T[key][row] = K . Q^T      A = K tile (LDS, 16-byte reads), B = Q (registers)
@@ -18,7 +28,8 @@
 //                                B = P^T, which is exactly the accumulator layout of
 //                                S^T after conversion to bf16 -- no data movement.
 // With v_mfma_f32_32x32x16_bf16 a lane holds 16 of the 32 keys of a sub-tile for its
-// row; the other 16 sit in lane+32, so row max / row sum cost one half-swap each.
+// row; the other 16 sit in lane+32, so a row max costs one half-swap.  The running
+// max is only raised (and O, l rescaled) when a tile exceeds it by more than 2^8.
 #include "ragc_internal.h"
 
 namespace ragc {
@@ -30,8 +41,17 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int TM = 128;  // rows per workgroup
-constexpr int TN = 64;   // keys per tile
+constexpr int TM = kAttnRowsPerItem;  // rows per work item
+constexpr int TN = 64;                // keys per tile
+constexpr float kRescaleThreshold = 8.f;  // log2 units
+
+// Wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane i's 16 bytes
+// land at lds_addr + 16*i.  Issued as inline assembly on purpose: the compiler's own
+// bookkeeping for this instruction drains every outstanding load before the next LDS read,
+// which would serialise the ring; the waits are placed by hand (wait_vmcnt + block_barrier).
+__device__ __forceinline__ void dma_16B_per_lane(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
 
 __device__ __forceinline__ float other_half(float x) {
     // value held by lane ^ 32
@@ -39,25 +59,58 @@ __device__ __forceinline__ float other_half(float x) {
     return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// XOR pattern applied to the 16-byte chunk index of row `row` (depends on row & 15).
 template <int D>
-struct Smem {
-    static constexpr int KS = D + 8;   // K row stride (elements): 16-byte reads of 16 rows hit distinct banks
-    static constexpr int VS = D + 32;  // V row stride: 4 rows x 64 bytes of a transposing read hit distinct banks
-    __bf16 k[TN][KS];
-    __bf16 v[TN][VS];
-};
+__device__ __forceinline__ int swz(int row) {
+    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
 
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
-    constexpr int CPR = D / 8;               // 16-byte chunks per K/V row
-    constexpr int LD = TN * CPR / 256;       // chunks per thread per tile and plane
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+__device__ __forceinline__ void block_barrier() {
+    // hardware barrier without the fence of __syncthreads(): outstanding LDS-DMA loads of
+    // later tiles must stay in flight across it
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int D, int NG, int RING>
+__global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn_bf16_kernel(AttnLaunch a, AttnWorkList wl) {
+    constexpr int CPR = D / 8;          // 16-byte chunks per K/V row
+    constexpr int ROWB = D * 2;         // bytes per row
+    constexpr int PLANEB = TN * ROWB;   // one tile of K (or V)
+    constexpr int STAGEB = 2 * PLANEB;
+    constexpr int RPI = 64 / CPR;       // rows covered by one wave-wide 1 KiB DMA instruction
+    constexpr int IPB = 16 / RPI;       // DMA instructions per 16-row block and plane
+    constexpr int LPS = 2 * IPB;        // DMA instructions per wave and step
     constexpr int KSTEPS = D / 16;
     constexpr int DT = D / 32;
-    __shared__ Smem<D> sm;
+    constexpr int NSTAGE = NG * RING;
+    static_assert(NSTAGE * STAGEB <= 160 * 1024, "LDS");
+    __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGEB];
 
-    const int r = blockIdx.z;
-    const int g = blockIdx.y;
-    const int tile = gridDim.x - 1 - blockIdx.x;  // long key ranges first
+    // ---- work item: consecutive workgroup ids round-robin over the 8 XCDs, so the kv head
+    // is taken from the low bits: all row tiles of one (request, kv head) stream share an L2
+    const int Hkv = a.b.kv_heads;
+    int g, item;
+    if ((Hkv & 7) == 0) {
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3, hpx = Hkv >> 3;
+        g = x + 8 * (j % hpx);
+        item = j / hpx;
+    } else {
+        g = blockIdx.x % Hkv;
+        item = blockIdx.x / Hkv;
+    }
+    const uint32_t packed = wl.item[item];
+    const int r = packed >> 16, tile = packed & 0xffff;
+
     const int G = a.group;
     const int N = a.b.new_len[r];
     const int rows_total = N * G;
@@ -65,9 +118,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
     if (row0 >= rows_total) return;
     const int P = a.b.prefix_len[r];
     const int s0 = a.b.new_start[r];
-    const int Hkv = a.b.kv_heads;
     const int Hq = a.q_heads;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = w >> 2, wq = w & 3;
 
     const __bf16* __restrict__ q = static_cast<const __bf16*>(a.q);
     const __bf16* __restrict__ k_new = static_cast<const __bf16*>(a.k_new);
@@ -77,17 +131,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
     const int32_t* __restrict__ table = a.b.block_table + (long long)r * a.b.table_stride;
 
     const int last_row = min(row0 + TM, rows_total) - 1;
-    const int kv_limit = P + last_row / G + 1;  // keys [0, kv_limit) are visible to some row of the tile
+    const int kv_limit = P + last_row / G + 1;  // keys [0, kv_limit) are visible to some row of the item
     const int ntiles = (kv_limit + TN - 1) / TN;
+    const int nsteps = (ntiles + NG - 1) / NG;  // group `grp` takes tile step*NG + grp
 
-    // fused append: this workgroup owns the tokens whose first row (head 0 of the group) it holds
+    // ---- fused append: this work item owns the tokens whose first row (head 0 of the group) it holds
     if (a.fused_append) {
         const int tok_lo = (row0 + G - 1) / G;
         const int tok_hi = min(N - 1, (row0 + TM - 1) / G);
         __bf16* wk = static_cast<__bf16*>(a.pool_k_w);
         __bf16* wv = static_cast<__bf16*>(a.pool_v_w);
         const int n = (tok_hi - tok_lo + 1) * CPR;
-        for (int idx = tid; idx < n; idx += 256) {
+        for (int idx = tid; idx < n; idx += 256 * NG) {
             const int tok = tok_lo + idx / CPR, ch = idx % CPR;
             const int pos = P + tok;
             const long long src = ((long long)(s0 + tok) * Hkv + g) * D + ch * 8;
@@ -97,14 +152,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
         }
     }
 
-    // this lane's query row
-    const int my_row = min(row0 + w * 32 + l32, rows_total - 1);  // clamped: rows past the end repeat the last one
+    // ---- this lane's query row
+    const int wrow0 = row0 + wq * 32;
+    const int my_row = min(wrow0 + l32, rows_total - 1);  // rows past the end repeat the last one
     const int my_tok = my_row / G;
     const int my_head = g * G + (my_row - my_tok * G);
     const int my_vis = P + my_tok + 1;  // keys [0, my_vis) are visible to this row
-    const bool wave_active = row0 + w * 32 < rows_total;
-    const int wave_vis_min = P + (row0 + w * 32) / G + 1;
-    const int wave_vis_max = P + min(row0 + w * 32 + 31, rows_total - 1) / G + 1;
+    const bool wave_active = wrow0 < rows_total;
+    const int wave_vis_min = P + wrow0 / G + 1;
+    const int wave_vis_max = P + min(wrow0 + 31, rows_total - 1) / G + 1;
 
     bf16x8 qreg[KSTEPS];
     {
@@ -112,58 +168,94 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
+    // Every ordinary load above completes here, before the DMA ring starts counting.  The
+    // empty asm statements make the compiler itself wait for the Q registers now; otherwise it
+    // would place its vmcnt waits at their first use inside the loop and drain the ring there.
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) asm volatile("" ::"v"(qreg[ks]));
+    wait_vmcnt<0>();
+
+    // ---- DMA: wave (grp, wq) copies block wq (16 keys) of tile step*NG+grp, K and V planes
+    int dma_row16[IPB], dma_chunk[IPB];
+#pragma unroll
+    for (int c = 0; c < IPB; ++c) {
+        dma_row16[c] = RPI * c + lane / CPR;
+        dma_chunk[c] = (lane % CPR) ^ swz<D>(dma_row16[c]);
+    }
+    // Block ids are fetched 64 steps at a time, one per lane (entry of step blk_base+lane),
+    // and handed out with a lane read: no memory load sits on the issue path of a step.
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    int blk_vec = 0, blk_base = -64;
+    auto issue = [&](int step) {
+        if (step - blk_base >= 64) {
+            blk_base = step;
+            const int e = (min((step + lane) * NG + grp, ntiles - 1) * TN >> 4) + wq;
+            blk_vec = (e << 4) < P ? table[e] : 0;
+            asm volatile("" ::"v"(blk_vec));  // the compiler's wait for this load stays inside the branch
+        }
+        const int tg = min(step * NG + grp, ntiles - 1);  // a group without a tile re-reads the last one (same count of loads)
+        const int kbase = tg * TN + wq * 16;
+        const int blk = __builtin_amdgcn_readlane(blk_vec, step - blk_base);
+        const uint32_t stage = smem_addr + ((step % RING) * NG + grp) * STAGEB;
+#pragma unroll
+        for (int c = 0; c < IPB; ++c) {
+            const int kj = kbase + dma_row16[c];
+            long long off;
+            if (kj < P) {
+                off = (long long)blk * a.b.block_stride + ((long long)g * kBlock + dma_row16[c]) * D + dma_chunk[c] * 8;
+            } else {
+                const int kn = min(kj, kv_limit - 1) - P;  // rows past the horizon re-read the last visible one
+                off = ((long long)(s0 + kn) * Hkv + g) * D + dma_chunk[c] * 8;
+            }
+            const __bf16* ksrc = (kj < P ? pool_k : k_new) + off;
+            const __bf16* vsrc = (kj < P ? pool_v : v_new) + off;
+            const uint32_t dst = stage + (wq * 16 + RPI * c) * ROWB;
+            dma_16B_per_lane(ksrc, dst);
+            dma_16B_per_lane(vsrc, dst + PLANEB);
+        }
+    };
+
+    // ---- per-lane LDS read offsets (bytes, within a stage)
+    // K, A operand of S^T: row sub*32+l32, chunk 2*ks+hf
+    int koff[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) koff[ks] = l32 * ROWB + (((2 * ks + hf) ^ swz<D>(l32)) << 4);
+    // V, A operand of O^T (transposing read): rows kk*16 + 8*h2 + 4*hf + (lane&15)/4 + {sub*32},
+    // 8 bytes at element dt*32 + 16*((lane>>4)&1) + 4*(lane&3)
+    int voff[2][DT];
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const int row = 8 * h2 + 4 * hf + ((lane & 15) >> 2);
+            const int elem = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+            voff[h2][dt] = PLANEB + row * ROWB + ((((elem >> 3)) ^ swz<D>(row)) << 4) + (elem & 7) * 2;
+        }
 
     f32x16 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
-    float m_run = -INFINITY;  // running max of scaled scores (log2 domain)
+    float m_run = -INFINITY;  // reference exponent of O and l (log2 domain); at most 2^8 below the true row max
     float l_run = 0.f;        // this lane's partial of the running sum (other half in lane^32)
     const float c = a.scale_log2e;
 
-    // global -> registers for one tile (zero beyond kv_limit: stale pool slots may hold anything)
-    u32x4 kbuf[LD], vbuf[LD];
-    auto prefetch = [&](int t) {
 #pragma unroll
-        for (int it = 0; it < LD; ++it) {
-            const int idx = tid + it * 256;
-            const int row = idx / CPR, ch = idx % CPR;
-            const int kj = t * TN + row;
-            u32x4 kk = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-            if (kj < kv_limit) {
-                if (kj < P) {
-                    const long long off = (long long)table[kj >> 4] * a.b.block_stride + ((long long)g * kBlock + (kj & 15)) * D + ch * 8;
-                    kk = *reinterpret_cast<const u32x4*>(pool_k + off);
-                    vv = *reinterpret_cast<const u32x4*>(pool_v + off);
-                } else {
-                    const long long off = ((long long)(s0 + kj - P) * Hkv + g) * D + ch * 8;
-                    kk = *reinterpret_cast<const u32x4*>(k_new + off);
-                    vv = *reinterpret_cast<const u32x4*>(v_new + off);
-                }
-            }
-            kbuf[it] = kk;
-            vbuf[it] = vv;
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int it = 0; it < LD; ++it) {
-            const int idx = tid + it * 256;
-            const int row = idx / CPR, ch = idx % CPR;
-            *reinterpret_cast<u32x4*>(&sm.k[row][ch * 8]) = kbuf[it];
-            *reinterpret_cast<u32x4*>(&sm.v[row][ch * 8]) = vbuf[it];
-        }
-    };
+    for (int s = 0; s < RING - 1; ++s)
+        if (s < nsteps) issue(s);
 
-    prefetch(0);
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();  // every wave is done reading the previous tile
-        stash();
-        __syncthreads();
-        if (t + 1 < ntiles) prefetch(t + 1);  // in flight while this tile is computed
-        const int base = t * TN;
-        if (!wave_active || base >= wave_vis_max) continue;
+    for (int step = 0; step < nsteps; ++step) {
+        // loads of this step have landed (later steps may stay in flight)
+        if (RING > 2 && step + RING - 2 < nsteps) wait_vmcnt<(RING - 2) * LPS>();
+        else wait_vmcnt<0>();
+        block_barrier();  // every wave's part is in LDS, and every wave is done with the previous step
+        if (step + RING - 1 < nsteps) issue(step + RING - 1);
+
+        const int tg = step * NG + grp;
+        const int base = tg * TN;
+        if (!wave_active || tg >= ntiles || base >= wave_vis_max) continue;
+        const char* stage = smem + ((step % RING) * NG + grp) * STAGEB;
 
         // S^T = K Q^T
         f32x16 sacc[2];
@@ -175,7 +267,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
         for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&sm.k[sub * 32 + l32][ks * 16 + hf * 8]);
+                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(stage + sub * 32 * ROWB + koff[ks]);
                 sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], sacc[sub], 0, 0, 0);
             }
         }
@@ -196,38 +288,43 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[sub][i]);
         mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m_run, mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        const float m_tile = mx * c;
+        const bool raise = m_tile > m_run + kRescaleThreshold;  // true on a row's first tile (m_run = -inf)
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            // 1 where nothing changes, 0 on a row's first visible tile (exp2(-inf))
+            const float alpha = raise ? __builtin_amdgcn_exp2f(m_run - m_tile) : 1.f;
+            m_run = raise ? m_tile : m_run;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+        }
+        // a row that has not seen a key yet (possible in the second wave group) has m_run = -inf
+        // and only masked scores: subtract 0 instead, so that exp2(-inf - 0) = 0 and not NaN
+        const float m_sub = m_run == -INFINITY ? 0.f : m_run;
         float psum = 0.f;
         bf16x8 pb[2][2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(sacc[sub][i] * c - m_new);
+                const float p = __builtin_amdgcn_exp2f(sacc[sub][i] * c - m_sub);
                 psum += p;
                 pb[sub][i >> 3][i & 7] = (__bf16)p;
             }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+        l_run += psum;
 
         // O^T += V^T P^T ; V rows fetched with the transposing LDS read
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const int vrow = sub * 32 + kk * 16 + hf * 4 + ((lane & 15) >> 2);
-                const int vcol = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+                const char* vb = stage + (sub * 32 + kk * 16) * ROWB;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4*)(&sm.v[vrow][dt * 32 + vcol]));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4*)(&sm.v[vrow + 8][dt * 32 + vcol]));
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + voff[0][dt]));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + voff[1][dt]));
                     const bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo);
                     const bf16x4 hi_b = __builtin_bit_cast(bf16x4, hi);
                     const bf16x8 va = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -236,11 +333,40 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
             }
     }
 
-    // normalise and store: lane holds 4 consecutive d per (dt, i/4)
+    // ---- merge the wave groups through LDS (the DMA ring is idle now)
+    if (NG > 1) {
+        float* xf = reinterpret_cast<float*>(smem);
+        constexpr int WSTRIDE = (DT * 16 + 2) * 64;  // floats per wave
+        block_barrier();
+        if (grp == 1) {
+            float* dst = xf + wq * WSTRIDE + lane;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dst[(dt * 16 + i) * 64] = oacc[dt][i];
+            dst[DT * 16 * 64] = m_run;
+            dst[(DT * 16 + 1) * 64] = l_run;
+        }
+        block_barrier();
+        if (grp == 1) return;
+        if (wave_active) {
+            const float* src = xf + wq * WSTRIDE + lane;
+            const float m1 = src[DT * 16 * 64], l1 = src[(DT * 16 + 1) * 64];
+            const float m = fmaxf(m_run, m1);  // group 0 always saw key 0: finite
+            const float s0f = __builtin_amdgcn_exp2f(m_run - m), s1f = __builtin_amdgcn_exp2f(m1 - m);
+            l_run = l_run * s0f + l1 * s1f;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[dt][i] = oacc[dt][i] * s0f + src[(dt * 16 + i) * 64] * s1f;
+        }
+    }
+
+    // ---- normalise and store: lane holds 4 consecutive d per (dt, i/4)
     if (!wave_active) return;
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.f / l_tot;
-    if (row0 + w * 32 + l32 < rows_total) {
+    if (wrow0 + l32 < rows_total) {
         __bf16* op = static_cast<__bf16*>(a.out) + ((long long)(s0 + my_tok) * Hq + my_head) * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -254,15 +380,33 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(AttnLaunch a) {
     }
 }
 
+template <int D, int NG, int RING>
+void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+}
+
 }  // namespace
 
-hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s) {
-    if (a.max_new <= 0 || a.b.num_reqs <= 0) return hipSuccess;
-    dim3 grid(((long long)a.max_new * a.group + TM - 1) / TM, a.b.kv_heads, a.b.num_reqs);
-    if (a.b.head_dim == 64)
-        hipLaunchKernelGGL(attn_bf16_kernel<64>, grid, dim3(256), 0, s, a);
-    else
-        hipLaunchKernelGGL(attn_bf16_kernel<128>, grid, dim3(256), 0, s, a);
+int attn_bf16_item_cost(int prefix, int new_len, int group, int tile) {
+    const int rows = new_len * group;
+    const int last_row = (tile + 1) * TM < rows ? (tile + 1) * TM - 1 : rows - 1;
+    return (prefix + last_row / group + 1 + TN - 1) / TN;
+}
+
+hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s) {
+    if (wl.n <= 0) return hipSuccess;
+    const bool d64 = a.b.head_dim == 64;
+    switch (variant) {
+        case kAttnVariantTwoGroups:
+            d64 ? launch_one<64, 2, 2>(a, wl, s) : launch_one<128, 2, 2>(a, wl, s);
+            break;
+        case kAttnVariantDeepRing:
+            d64 ? launch_one<64, 1, 4>(a, wl, s) : launch_one<128, 1, 4>(a, wl, s);
+            break;
+        default:
+            d64 ? launch_one<64, 1, 2>(a, wl, s) : launch_one<128, 1, 2>(a, wl, s);
+            break;
+    }
     return hipGetLastError();
 }
 

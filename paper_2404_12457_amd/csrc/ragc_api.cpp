@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -93,6 +94,20 @@ ragc::PagedBatch make_paged(const ragc_kv_pool* pool, const ragc_batch* b) {
     return pb;
 }
 
+// compute units of the current device (queried once per thread)
+int cu_count() {
+    thread_local int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
 int hip_fail(hipError_t e, const char* what) {
     return fail(RAGC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
@@ -154,9 +169,37 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     a.fused_append = (flags & RAGC_ATTN_APPEND_FUSED) ? 1 : 0;
     a.max_new = info.max_new;
     a.total_new = (int32_t)info.total_new;
-    const hipError_t e = pool->dtype == RAGC_DTYPE_BF16 ? ragc::launch_attn_bf16(a, static_cast<hipStream_t>(stream))
-                                                        : ragc::launch_attn_f32(a, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (pool->dtype == RAGC_DTYPE_F32) {
+        const hipError_t e = ragc::launch_attn_f32(a, s);
+        if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
+        return RAGC_OK;
+    }
+    // bf16: work items (request, 128-row tile), most key tiles first so the long ones start early
+    struct Item {
+        int32_t cost;
+        uint32_t packed;
+    };
+    std::vector<Item> items;
+    for (int r = 0; r < batch->num_reqs; ++r) {
+        const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
+        const int64_t rows = (int64_t)n * a.group;
+        const int tiles = (int)((rows + ragc::kAttnRowsPerItem - 1) / ragc::kAttnRowsPerItem);
+        if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
+        for (int t = 0; t < tiles; ++t)
+            items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t), (uint32_t)r << 16 | (uint32_t)t});
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.cost > y.cost; });
+    const int64_t workgroups = (int64_t)items.size() * pool->kv_heads;
+    int variant = workgroups >= 2 * (int64_t)cu_count() ? ragc::kAttnVariantOneGroup : ragc::kAttnVariantTwoGroups;
+    if (const char* force = std::getenv("RAGC_ATTN_VARIANT")) variant = std::atoi(force);
+    for (size_t i = 0; i < items.size(); i += ragc::kAttnMaxItems) {
+        ragc::AttnWorkList wl;
+        wl.n = (int32_t)std::min<size_t>(ragc::kAttnMaxItems, items.size() - i);
+        for (int j = 0; j < wl.n; ++j) wl.item[j] = items[i + j].packed;
+        const hipError_t e = ragc::launch_attn_bf16(a, wl, variant, s);
+        if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
+    }
     return RAGC_OK;
 }
 

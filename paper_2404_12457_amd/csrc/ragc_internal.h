@@ -40,7 +40,24 @@ struct AttnLaunch {
 };
 
 hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
-hipError_t launch_attn_bf16(const AttnLaunch& a, hipStream_t s);
+
+// bf16 path: the host orders the (request, row tile) work items by cost and passes
+// them in the kernel argument buffer (no device staging); long lists go out in
+// several launches.
+constexpr int kAttnRowsPerItem = 128;
+constexpr int kAttnMaxItems = 896;
+struct AttnWorkList {
+    int32_t n;
+    uint32_t item[kAttnMaxItems];  // request << 16 | row tile
+};
+enum AttnVariant {
+    kAttnVariantOneGroup = 0,   // 4 waves per workgroup, two workgroups per CU
+    kAttnVariantTwoGroups = 1,  // 8 waves per workgroup on alternating key tiles
+    kAttnVariantDeepRing = 2    // 4 waves, four-stage ring (three tiles in flight)
+};
+// number of 64-key tiles the work item (row tile `tile` of a request) walks
+int attn_bf16_item_cost(int prefix, int new_len, int group, int tile);
+hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s);
 
 hipError_t launch_append(const PagedBatch& b, void* pool_k, void* pool_v, const void* k_new, const void* v_new,
                          int32_t total_new, int esize, hipStream_t s);
