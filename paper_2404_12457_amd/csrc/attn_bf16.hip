@@ -30,6 +30,8 @@
 // With v_mfma_f32_32x32x16_bf16 a lane holds 16 of the 32 keys of a sub-tile for its
 // row; the other 16 sit in lane+32, so a row max costs one half-swap.  The running
 // max is only raised (and O, l rescaled) when a tile exceeds it by more than 2^8.
+#include <type_traits>
+
 #include "ragc_internal.h"
 
 namespace ragc {
@@ -51,6 +53,16 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 // which would serialise the ring; the waits are placed by hand (wait_vmcnt + block_barrier).
 __device__ __forceinline__ void dma_16B_per_lane(const void* gptr, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+// same with a wave-uniform base address and a 32-bit per-lane byte offset
+__device__ __forceinline__ void dma_16B_per_lane(uint64_t sbase, uint32_t lane_off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase) : "memory", "m0");
+}
+__device__ __forceinline__ uint64_t uniform_u64(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
 
 __device__ __forceinline__ float other_half(float x) {
@@ -121,7 +133,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int Hq = a.q_heads;
     const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = w >> 2, wq = w & 3;
+    const int grp = NG == 1 ? 0 : w >> 2, wq = w & 3;
 
     const __bf16* __restrict__ q = static_cast<const __bf16*>(a.q);
     const __bf16* __restrict__ k_new = static_cast<const __bf16*>(a.k_new);
@@ -175,12 +187,16 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     for (int ks = 0; ks < KSTEPS; ++ks) asm volatile("" ::"v"(qreg[ks]));
     wait_vmcnt<0>();
 
-    // ---- DMA: wave (grp, wq) copies block wq (16 keys) of tile step*NG+grp, K and V planes
-    int dma_row16[IPB], dma_chunk[IPB];
+    // ---- DMA: wave (grp, wq) copies block wq (16 keys) of tile step*NG+grp, K and V planes.
+    // Lane i of DMA instruction c brings row RPI*c + i/CPR of the block, 16-byte chunk
+    // (i%CPR) ^ swz(row): the swizzle is applied on the global side, LDS is written linearly.
+    uint32_t pool_loff[IPB], new_loff[IPB];  // byte offsets of this lane's chunk inside a pool block / a run of fresh rows
 #pragma unroll
     for (int c = 0; c < IPB; ++c) {
-        dma_row16[c] = RPI * c + lane / CPR;
-        dma_chunk[c] = (lane % CPR) ^ swz<D>(dma_row16[c]);
+        const int row16 = RPI * c + lane / CPR;
+        const int chunk = (lane % CPR) ^ swz<D>(row16);
+        pool_loff[c] = (row16 * D + chunk * 8) * 2;
+        new_loff[c] = (row16 * Hkv * D + chunk * 8) * 2;
     }
     // Block ids are fetched 64 steps at a time, one per lane (entry of step blk_base+lane),
     // and handed out with a lane read: no memory load sits on the issue path of a step.
@@ -196,30 +212,61 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         const int tg = min(step * NG + grp, ntiles - 1);  // a group without a tile re-reads the last one (same count of loads)
         const int kbase = tg * TN + wq * 16;
         const int blk = __builtin_amdgcn_readlane(blk_vec, step - blk_base);
-        const uint32_t stage = smem_addr + ((step % RING) * NG + grp) * STAGEB;
+        const uint32_t dst = smem_addr + (grp * RING + step % RING) * STAGEB + wq * 16 * ROWB;
+        if (kbase + 16 <= P) {
+            // the whole block is cached: one pool block, uniform base + per-lane constant
+            const long long boff = ((long long)blk * a.b.block_stride + (long long)g * kBlock * D) * 2;
+            const uint64_t kb = uniform_u64(reinterpret_cast<const char*>(pool_k) + boff);
+            const uint64_t vb = uniform_u64(reinterpret_cast<const char*>(pool_v) + boff);
 #pragma unroll
-        for (int c = 0; c < IPB; ++c) {
-            const int kj = kbase + dma_row16[c];
-            long long off;
-            if (kj < P) {
-                off = (long long)blk * a.b.block_stride + ((long long)g * kBlock + dma_row16[c]) * D + dma_chunk[c] * 8;
-            } else {
-                const int kn = min(kj, kv_limit - 1) - P;  // rows past the horizon re-read the last visible one
-                off = ((long long)(s0 + kn) * Hkv + g) * D + dma_chunk[c] * 8;
+            for (int c = 0; c < IPB; ++c) {
+                dma_16B_per_lane(kb, pool_loff[c], dst + RPI * c * ROWB);
+                dma_16B_per_lane(vb, pool_loff[c], dst + RPI * c * ROWB + PLANEB);
             }
-            const __bf16* ksrc = (kj < P ? pool_k : k_new) + off;
-            const __bf16* vsrc = (kj < P ? pool_v : v_new) + off;
-            const uint32_t dst = stage + (wq * 16 + RPI * c) * ROWB;
-            dma_16B_per_lane(ksrc, dst);
-            dma_16B_per_lane(vsrc, dst + PLANEB);
+        } else if (kbase >= P && kbase + 16 <= kv_limit) {
+            // 16 fresh rows, all inside the horizon
+            const long long boff = (((long long)(s0 + kbase - P)) * Hkv + g) * D * 2;
+            const uint64_t kb = uniform_u64(reinterpret_cast<const char*>(k_new) + boff);
+            const uint64_t vb = uniform_u64(reinterpret_cast<const char*>(v_new) + boff);
+#pragma unroll
+            for (int c = 0; c < IPB; ++c) {
+                dma_16B_per_lane(kb, new_loff[c], dst + RPI * c * ROWB);
+                dma_16B_per_lane(vb, new_loff[c], dst + RPI * c * ROWB + PLANEB);
+            }
+        } else {
+            // the block straddles the prefix end or the horizon: choose the source per row;
+            // rows past the horizon re-read the last visible one (they are masked later)
+#pragma unroll
+            for (int c = 0; c < IPB; ++c) {
+                const int row16 = RPI * c + lane / CPR;
+                const int chunk = (lane % CPR) ^ swz<D>(row16);
+                const int kj = kbase + row16;
+                long long off;
+                if (kj < P) {
+                    off = (long long)blk * a.b.block_stride + ((long long)g * kBlock + row16) * D + chunk * 8;
+                } else {
+                    const int kn = min(kj, kv_limit - 1) - P;
+                    off = ((long long)(s0 + kn) * Hkv + g) * D + chunk * 8;
+                }
+                const __bf16* ksrc = (kj < P ? pool_k : k_new) + off;
+                const __bf16* vsrc = (kj < P ? pool_v : v_new) + off;
+                dma_16B_per_lane(ksrc, dst + RPI * c * ROWB);
+                dma_16B_per_lane(vsrc, dst + RPI * c * ROWB + PLANEB);
+            }
         }
     };
 
-    // ---- per-lane LDS read offsets (bytes, within a stage)
+    // ---- per-lane LDS read offsets (bytes); the stage and sub-tile parts are immediates
+    typedef __attribute__((address_space(3))) char lds_char;
+    lds_char* const lds0 = (lds_char*)smem;
+    const int grp_off = grp * RING * STAGEB;  // folded into the per-lane offsets below
     // K, A operand of S^T: row sub*32+l32, chunk 2*ks+hf
     int koff[KSTEPS];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) koff[ks] = l32 * ROWB + (((2 * ks + hf) ^ swz<D>(l32)) << 4);
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        koff[ks] = grp_off + l32 * ROWB + (((2 * ks + hf) ^ swz<D>(l32)) << 4);
+        asm volatile("" : "+v"(koff[ks]));  // keep it one register: address = this + immediate
+    }
     // V, A operand of O^T (transposing read): rows kk*16 + 8*h2 + 4*hf + (lane&15)/4 + {sub*32},
     // 8 bytes at element dt*32 + 16*((lane>>4)&1) + 4*(lane&3)
     int voff[2][DT];
@@ -229,7 +276,8 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int dt = 0; dt < DT; ++dt) {
             const int row = 8 * h2 + 4 * hf + ((lane & 15) >> 2);
             const int elem = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-            voff[h2][dt] = PLANEB + row * ROWB + ((((elem >> 3)) ^ swz<D>(row)) << 4) + (elem & 7) * 2;
+            voff[h2][dt] = grp_off + row * ROWB + ((((elem >> 3)) ^ swz<D>(row)) << 4) + (elem & 7) * 2;
+            asm volatile("" : "+v"(voff[h2][dt]));
         }
 
     f32x16 oacc[DT];
@@ -241,11 +289,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     float l_run = 0.f;        // this lane's partial of the running sum (other half in lane^32)
     const float c = a.scale_log2e;
 
-#pragma unroll
-    for (int s = 0; s < RING - 1; ++s)
-        if (s < nsteps) issue(s);
-
-    for (int step = 0; step < nsteps; ++step) {
+    // one step with the ring slot as a compile-time constant
+    auto do_step = [&](int step, auto slot_c) {
+        constexpr int SLOT = decltype(slot_c)::value;
         // loads of this step have landed (later steps may stay in flight)
         if (RING > 2 && step + RING - 2 < nsteps) wait_vmcnt<(RING - 2) * LPS>();
         else wait_vmcnt<0>();
@@ -254,8 +300,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 
         const int tg = step * NG + grp;
         const int base = tg * TN;
-        if (!wave_active || tg >= ntiles || base >= wave_vis_max) continue;
-        const char* stage = smem + ((step % RING) * NG + grp) * STAGEB;
+        if (!wave_active || tg >= ntiles || base >= wave_vis_max) return;
+        lds_char* const kst = lds0 + SLOT * STAGEB;
+        lds_char* const vst = kst + PLANEB;
 
         // S^T = K Q^T
         f32x16 sacc[2];
@@ -267,7 +314,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(stage + sub * 32 * ROWB + koff[ks]);
+                const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks]);
                 sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], sacc[sub], 0, 0, 0);
             }
         }
@@ -289,7 +336,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[sub][i]);
         mx = fmaxf(mx, other_half(mx));
         const float m_tile = mx * c;
-        const bool raise = m_tile > m_run + kRescaleThreshold;  // true on a row's first tile (m_run = -inf)
+        const bool raise = m_tile > m_run + kRescaleThreshold;  // true on a row's first visible tile (m_run = -inf)
         if (__builtin_amdgcn_ballot_w64(raise) != 0) {
             // 1 where nothing changes, 0 on a row's first visible tile (exp2(-inf))
             const float alpha = raise ? __builtin_amdgcn_exp2f(m_run - m_tile) : 1.f;
@@ -320,7 +367,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const char* vb = stage + (sub * 32 + kk * 16) * ROWB;
+                lds_char* const vb = vst + (sub * 32 + kk * 16) * ROWB;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
                     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vb + voff[0][dt]));
@@ -331,6 +378,19 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
                     oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[sub][kk], oacc[dt], 0, 0, 0);
                 }
             }
+    };
+
+#pragma unroll
+    for (int s = 0; s < RING - 1; ++s)
+        if (s < nsteps) issue(s);
+
+    for (int step0 = 0; step0 < nsteps; step0 += RING) {
+        do_step(step0, std::integral_constant<int, 0>{});
+        if (step0 + 1 < nsteps) do_step(step0 + 1, std::integral_constant<int, 1>{});
+        if (RING > 2) {
+            if (step0 + 2 < nsteps) do_step(step0 + 2, std::integral_constant<int, 2 % RING>{});
+            if (step0 + 3 < nsteps) do_step(step0 + 3, std::integral_constant<int, 3 % RING>{});
+        }
     }
 
     // ---- merge the wave groups through LDS (the DMA ring is idle now)
