@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="configuration index for the headline line (2, 3 or 4)")
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations, append and swap figures")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run a plain 512 MiB device copy three times (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; the path issues no collective and --gpus > 1 is not supported")
@@ -124,6 +126,14 @@ def main():
     from paper_2404_12457_amd import workload as W
 
     B.load()  # fails loudly if libragc.so is missing
+    if args.calibrate_copy:
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)  # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     FUSED = B.RAGC_ATTN_APPEND_FUSED
     w = W.make_config(args.workload)
     wall_ms, ev_ms = bench_attention(w, args.steps, args.warmup, torch, harness, B, FUSED)
