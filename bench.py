@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="configuration index for the headline line (2, 3 or 4)")
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations, append and swap figures")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--pool-copies", type=int, default=4,
+                    help="pool copies rotated between steps (1 = every step re-reads the same, cache-warm buffers)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 512 MiB device copy three times (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -136,7 +138,7 @@ def main():
         torch.cuda.empty_cache()
     FUSED = B.RAGC_ATTN_APPEND_FUSED
     w = W.make_config(args.workload)
-    wall_ms, ev_ms = bench_attention(w, args.steps, args.warmup, torch, harness, B, FUSED)
+    wall_ms, ev_ms = bench_attention(w, args.steps, args.warmup, torch, harness, B, FUSED, copies=args.pool_copies)
     flops, nbytes = w.attn_flops(), attn_bytes(w, True)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     ach_gbs = nbytes / (ev_ms * 1e-3) / 1e9
@@ -158,7 +160,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "requests": w.num_reqs, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "prefix_tokens": int(w.prefix_len.sum()), "new_tokens": w.total_new,
-                   "block_size": 16, "pool_blocks": w.num_blocks, "fused_append": True, "pool_copies_rotated": 4},
+                   "block_size": 16, "pool_blocks": w.num_blocks, "fused_append": True, "pool_copies_rotated": args.pool_copies},
         "roofline": roof,
     }
 

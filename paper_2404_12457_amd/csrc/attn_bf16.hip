@@ -30,68 +30,12 @@
 // With v_mfma_f32_32x32x16_bf16 a lane holds 16 of the 32 keys of a sub-tile for its
 // row; the other 16 sit in lane+32, so a row max costs one half-swap.  The running
 // max is only raised (and O, l rescaled) when a tile exceeds it by more than 2^8.
-#include <type_traits>
-
-#include "ragc_internal.h"
+#include "attn_bf16_common.h"
 
 namespace ragc {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
 constexpr int TM = kAttnRowsPerItem;  // rows per work item
-constexpr int TN = 64;                // keys per tile
-constexpr float kRescaleThreshold = 8.f;  // log2 units
-
-// Wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane i's 16 bytes
-// land at lds_addr + 16*i.  Issued as inline assembly on purpose: the compiler's own
-// bookkeeping for this instruction drains every outstanding load before the next LDS read,
-// which would serialise the ring; the waits are placed by hand (wait_vmcnt + block_barrier).
-__device__ __forceinline__ void dma_16B_per_lane(const void* gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
-}
-// same with a wave-uniform base address and a 32-bit per-lane byte offset
-__device__ __forceinline__ void dma_16B_per_lane(uint64_t sbase, uint32_t lane_off, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase) : "memory", "m0");
-}
-__device__ __forceinline__ uint64_t uniform_u64(const void* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
-__device__ __forceinline__ float other_half(float x) {
-    // value held by lane ^ 32
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
-}
-
-// XOR pattern applied to the 16-byte chunk index of row `row` (depends on row & 15).
-template <int D>
-__device__ __forceinline__ int swz(int row) {
-    if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (N == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
-__device__ __forceinline__ void block_barrier() {
-    // hardware barrier without the fence of __syncthreads(): outstanding LDS-DMA loads of
-    // later tiles must stay in flight across it
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 template <int D, int NG, int RING>
 __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn_bf16_kernel(AttnLaunch a, AttnWorkList wl) {
@@ -447,14 +391,15 @@ void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
 
 }  // namespace
 
-int attn_bf16_item_cost(int prefix, int new_len, int group, int tile) {
+int attn_bf16_item_cost(int prefix, int new_len, int group, int tile, int rows_per_item) {
     const int rows = new_len * group;
-    const int last_row = (tile + 1) * TM < rows ? (tile + 1) * TM - 1 : rows - 1;
+    const int last_row = (tile + 1) * rows_per_item < rows ? (tile + 1) * rows_per_item - 1 : rows - 1;
     return (prefix + last_row / group + 1 + TN - 1) / TN;
 }
 
 hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s) {
     if (wl.n <= 0) return hipSuccess;
+    if (variant == kAttnVariantW64 || variant == kAttnVariantW64TwoGroups) return launch_attn_bf16_w64(a, wl, variant, s);
     const bool d64 = a.b.head_dim == 64;
     switch (variant) {
         case kAttnVariantTwoGroups:
