@@ -45,18 +45,31 @@ def _time_steps(fn, steps, warmup, torch):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
-def _rotating(w, copies, harness):
-    return [harness.DeviceWorkload(w) for _ in range(copies)]
+def _rotating(index, copies, harness, W, one_pool):
+    """`copies` instances of the configuration.  one_pool: the same data placed at disjoint
+    blocks of ONE pool (cold data, warm address translations: what a long-running server
+    sees); otherwise every instance has a pool of its own."""
+    w0 = W.make_config(index)
+    if copies == 1:
+        return w0, [harness.DeviceWorkload(w0)]
+    if not one_pool:
+        return w0, [harness.DeviceWorkload(w0) for _ in range(copies)]
+    per = int(sum((int(p) + int(n) + 15) // 16 for p, n in zip(w0.prefix_len, w0.new_len))) + 2  # blocks one placement can take
+    dws = [harness.DeviceWorkload(w0)]
+    for c in range(1, copies):
+        wc = W.make_config(index, placement_skip=c * per)
+        dws.append(harness.DeviceWorkload(wc, pool=(dws[0].pool_k, dws[0].pool_v)))
+    return w0, dws
 
 
-def bench_attention(w, steps, warmup, torch, harness, B, flags, copies=4):
-    dws = _rotating(w, copies, harness)
+def bench_attention(index, steps, warmup, torch, harness, B, W, flags, copies=4, one_pool=True):
+    w, dws = _rotating(index, copies, harness, W, one_pool)
     for d in dws:
         d.ensure_workspace(flags)
     wall_ms, ev_ms = _time_steps(lambda i: dws[i % copies].attn(flags), steps, warmup, torch)
     del dws
     torch.cuda.empty_cache()
-    return wall_ms, ev_ms
+    return w, wall_ms, ev_ms
 
 
 def attn_bytes(w, fused):
@@ -113,6 +126,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--pool-copies", type=int, default=4,
                     help="pool copies rotated between steps (1 = every step re-reads the same, cache-warm buffers)")
+    ap.add_argument("--separate-pools", action="store_true",
+                    help="give every rotated copy a pool of its own instead of disjoint blocks of one pool")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 512 MiB device copy three times (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -137,8 +152,8 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
     FUSED = B.RAGC_ATTN_APPEND_FUSED
-    w = W.make_config(args.workload)
-    wall_ms, ev_ms = bench_attention(w, args.steps, args.warmup, torch, harness, B, FUSED, copies=args.pool_copies)
+    w, wall_ms, ev_ms = bench_attention(args.workload, args.steps, args.warmup, torch, harness, B, W, FUSED,
+                                        copies=args.pool_copies, one_pool=not args.separate_pools)
     flops, nbytes = w.attn_flops(), attn_bytes(w, True)
     tflops = flops / (wall_ms * 1e-3) / 1e12
     ach_gbs = nbytes / (ev_ms * 1e-3) / 1e9
@@ -160,7 +175,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "requests": w.num_reqs, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "prefix_tokens": int(w.prefix_len.sum()), "new_tokens": w.total_new,
-                   "block_size": 16, "pool_blocks": w.num_blocks, "fused_append": True, "pool_copies_rotated": args.pool_copies},
+                   "block_size": 16, "pool_blocks": w.num_blocks, "fused_append": True, "placements_rotated": args.pool_copies, "one_pool": not args.separate_pools},
         "roofline": roof,
     }
 
@@ -170,8 +185,8 @@ def main():
         for idx in (1, 3, 4):
             if idx == args.workload:
                 continue
-            wx = W.make_config(idx)
-            wm, em = bench_attention(wx, steps2, warm2, torch, harness, B, FUSED, copies=4 if idx != 1 else 1)
+            wx, wm, em = bench_attention(idx, steps2, warm2, torch, harness, B, W, FUSED, copies=4 if idx != 1 else 1,
+                                         one_pool=not args.separate_pools)
             fl, by = wx.attn_flops(), attn_bytes(wx, True)
             extras[f"C{idx}"] = {"workload": wx.name, "ms_per_step": wm, "kernel_ms": em, "tflops": fl / em / 1e9,
                                  "new_tokens_per_s": wx.total_new / (wm * 1e-3), "mfma_frac": fl / em / 1e9 / MFMA_BF16_PEAK_TFLOPS,

@@ -87,9 +87,10 @@ typedef struct ragc_kv_pool {
  * starting at 0.  ragc_prefill_attn accepts any offsets (so a subset of a batch
  * can be launched over the same packed tensors); ragc_kv_append needs
  * new_start[r+1] = new_start[r] + new_len[r] (new_start[0] may be non-zero).
- * The h_* arrays are host copies of the same metadata: h_prefix_len, h_new_len
- * are required (the launch is sized from them); h_block_table is optional and,
- * when given, every entry the call will touch is range-checked. */
+ * The h_* arrays are host copies of the same metadata: h_prefix_len, h_new_len and
+ * h_new_start are required (the launch is sized from them and the work items carry
+ * them to the device in the kernel arguments); h_block_table is optional and, when
+ * given, every entry the call will touch is range-checked. */
 typedef struct ragc_batch {
     int32_t num_reqs;
     int32_t table_stride;          /* entries per block_table row */
@@ -99,6 +100,7 @@ typedef struct ragc_batch {
     const int32_t* block_table;    /* [device] [num_reqs][table_stride] */
     const int32_t* h_prefix_len;   /* [host] [num_reqs] */
     const int32_t* h_new_len;      /* [host] [num_reqs] */
+    const int32_t* h_new_start;    /* [host] [num_reqs+1] */
     const int32_t* h_block_table;  /* [host] optional */
 } ragc_batch;
 

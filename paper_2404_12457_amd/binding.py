@@ -36,7 +36,8 @@ class ragc_kv_pool(ctypes.Structure):
 class ragc_batch(ctypes.Structure):
     _fields_ = [("num_reqs", ctypes.c_int32), ("table_stride", ctypes.c_int32), ("prefix_len", ctypes.c_void_p),
                 ("new_len", ctypes.c_void_p), ("new_start", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
-                ("h_prefix_len", ctypes.c_void_p), ("h_new_len", ctypes.c_void_p), ("h_block_table", ctypes.c_void_p)]
+                ("h_prefix_len", ctypes.c_void_p), ("h_new_len", ctypes.c_void_p), ("h_new_start", ctypes.c_void_p),
+                ("h_block_table", ctypes.c_void_p)]
 
 
 class RagcError(RuntimeError):
@@ -102,10 +103,10 @@ def make_pool(k, v, num_blocks: int, kv_heads: int, head_dim: int, dtype: int, b
 
 
 def make_batch(num_reqs: int, table_stride: int, prefix_len, new_len, new_start, block_table, h_prefix_len: np.ndarray,
-               h_new_len: np.ndarray, h_block_table: Optional[np.ndarray] = None) -> ragc_batch:
+               h_new_len: np.ndarray, h_new_start: np.ndarray, h_block_table: Optional[np.ndarray] = None) -> ragc_batch:
     """Device arrays + host copies.  The caller keeps every array alive while the struct is used."""
     return ragc_batch(num_reqs, table_stride, _ptr(prefix_len), _ptr(new_len), _ptr(new_start), _ptr(block_table),
-                      _ptr(h_prefix_len), _ptr(h_new_len), _ptr(h_block_table))
+                      _ptr(h_prefix_len), _ptr(h_new_len), _ptr(h_new_start), _ptr(h_block_table))
 
 
 def ragc_version() -> int:

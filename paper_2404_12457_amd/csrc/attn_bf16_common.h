@@ -21,10 +21,12 @@ constexpr float kRescaleThreshold = 8.f;  // log2 units
 // bookkeeping for this instruction drains every outstanding load before the next LDS read,
 // which would serialise the ring; the waits are placed by hand (wait_vmcnt + block_barrier).
 __device__ __forceinline__ void dma_16B_per_lane(const void* gptr, uint32_t lds_addr) {
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);  // wave-uniform by construction; make the register class explicit
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 // same with a wave-uniform base address and a 32-bit per-lane byte offset
 __device__ __forceinline__ void dma_16B_per_lane(uint64_t sbase, uint32_t lane_off, uint32_t lds_addr) {
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ uint64_t uniform_u64(const void* p) {

@@ -53,16 +53,16 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_w64_kernel(AttnLaunch a, Att
         g = blockIdx.x % Hkv;
         item = blockIdx.x / Hkv;
     }
-    const uint32_t packed = wl.item[item];
-    const int r = packed >> 16, tile = packed & 0xffff;
+    const AttnItem it = wl.item[item];
+    const int r = it.req_tile >> 16, tile = it.req_tile & 0xffff;
 
     const int G = a.group;
-    const int N = a.b.new_len[r];
+    const int N = it.new_len;
     const int rows_total = N * G;
     const int row0 = tile * TMV;
     if (row0 >= rows_total) return;
-    const int P = a.b.prefix_len[r];
-    const int s0 = a.b.new_start[r];
+    const int P = it.prefix_len;
+    const int s0 = it.new_start;
     const int Hq = a.q_heads;
     const int tid = threadIdx.x, lane = tid & 63, hf = lane >> 5, l32 = lane & 31;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -79,23 +79,6 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_w64_kernel(AttnLaunch a, Att
     const int kv_limit = P + last_row / G + 1;  // keys [0, kv_limit) are visible to some row of the item
     const int ntiles = (kv_limit + TN - 1) / TN;
     const int nsteps = (ntiles + NG - 1) / NG;  // group `grp` takes tile T*NG + grp, T = 0 .. nsteps-1
-
-    // ---- fused append: this work item owns the tokens whose first row (head 0 of the group) it holds
-    if (a.fused_append) {
-        const int tok_lo = (row0 + G - 1) / G;
-        const int tok_hi = min(N - 1, (row0 + TMV - 1) / G);
-        __bf16* wk = static_cast<__bf16*>(a.pool_k_w);
-        __bf16* wv = static_cast<__bf16*>(a.pool_v_w);
-        const int n = (tok_hi - tok_lo + 1) * CPR;
-        for (int idx = tid; idx < n; idx += 256) {
-            const int tok = tok_lo + idx / CPR, ch = idx % CPR;
-            const int pos = P + tok;
-            const long long src = ((long long)(s0 + tok) * Hkv + g) * D + ch * 8;
-            const long long dst = (long long)table[pos >> 4] * a.b.block_stride + ((long long)g * kBlock + (pos & 15)) * D + ch * 8;
-            *reinterpret_cast<u32x4*>(wk + dst) = *reinterpret_cast<const u32x4*>(k_new + src);
-            *reinterpret_cast<u32x4*>(wv + dst) = *reinterpret_cast<const u32x4*>(v_new + src);
-        }
-    }
 
     // ---- this lane's two query rows (slab s = rows wrow0 + 32 s + l32)
     const int wrow0 = row0 + wq * 64;
@@ -377,6 +360,45 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_w64_kernel(AttnLaunch a, Att
         else pv(std::integral_constant<int, 3 % R>{}, std::integral_constant<int, 1>{});
     }
     wait_vmcnt<0>();
+
+    // ---- fused append (after the key loop: nothing waits for it, and the fresh rows are L2-hot
+    // because the loop has just read them as keys).  This work item owns the tokens whose first
+    // row (head 0 of the group) it holds; 16-byte chunks, four per thread in flight.
+    if (a.fused_append) {
+        const int tok_lo = (row0 + G - 1) / G;
+        const int tok_hi = min(N - 1, (row0 + TMV - 1) / G);
+        __bf16* wk = static_cast<__bf16*>(a.pool_k_w);
+        __bf16* wv = static_cast<__bf16*>(a.pool_v_w);
+        const int n = (tok_hi - tok_lo + 1) * CPR;
+        constexpr int UNR = 4;
+        for (int i0 = tid; i0 < n; i0 += 256 * UNR) {
+            int blk[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int idx = min(i0 + u * 256, n - 1);
+                blk[u] = table[(P + tok_lo + idx / CPR) >> 4];
+            }
+            u32x4 kk[UNR], vv[UNR];
+            long long dst[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int idx = min(i0 + u * 256, n - 1);
+                const int tok = tok_lo + idx / CPR, ch = idx % CPR;
+                const int pos = P + tok;
+                const long long src = ((long long)(s0 + tok) * Hkv + g) * D + ch * 8;
+                dst[u] = (long long)blk[u] * a.b.block_stride + ((long long)g * kBlock + (pos & 15)) * D + ch * 8;
+                kk[u] = *reinterpret_cast<const u32x4*>(k_new + src);
+                vv[u] = *reinterpret_cast<const u32x4*>(v_new + src);
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                if (i0 + u * 256 < n) {
+                    *reinterpret_cast<u32x4*>(wk + dst[u]) = kk[u];
+                    *reinterpret_cast<u32x4*>(wv + dst[u]) = vv[u];
+                }
+            }
+        }
+    }
 
     // ---- merge the wave groups through LDS (the rings are idle now)
     if (NG > 1) {

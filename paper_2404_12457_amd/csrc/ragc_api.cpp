@@ -55,13 +55,15 @@ int check_batch(const ragc_kv_pool* pool, const ragc_batch* b, bool need_device,
     if (!b) return fail(RAGC_ERR_NULL, "batch is NULL");
     if (b->num_reqs < 0 || b->num_reqs > 65535) return fail(RAGC_ERR_SHAPE, "num_reqs %d", b->num_reqs);
     if (b->num_reqs == 0) return RAGC_OK;
-    if (!b->h_prefix_len || !b->h_new_len) return fail(RAGC_ERR_NULL, "h_prefix_len / h_new_len (host copies) are required");
+    if (!b->h_prefix_len || !b->h_new_len || !b->h_new_start)
+        return fail(RAGC_ERR_NULL, "h_prefix_len / h_new_len / h_new_start (host copies) are required");
     if (need_device && (!b->prefix_len || !b->new_len || !b->new_start || !b->block_table))
         return fail(RAGC_ERR_NULL, "a device array of the batch is NULL");
     if (b->table_stride <= 0) return fail(RAGC_ERR_SHAPE, "table_stride %d", b->table_stride);
     for (int r = 0; r < b->num_reqs; ++r) {
         const int64_t p = b->h_prefix_len[r], n = b->h_new_len[r];
         if (p < 0 || n < 0) return fail(RAGC_ERR_RANGE, "request %d: prefix_len %lld, new_len %lld", r, (long long)p, (long long)n);
+        if (b->h_new_start[r] < 0) return fail(RAGC_ERR_RANGE, "request %d: new_start %d", r, b->h_new_start[r]);
         const int64_t blocks = (p + n + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE;
         if (blocks > b->table_stride)
             return fail(RAGC_ERR_RANGE, "request %d: %lld tokens need %lld table entries, table_stride is %d", r, (long long)(p + n), (long long)blocks, b->table_stride);
@@ -178,7 +180,7 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     // bf16: work items (request, 128-row tile), most key tiles first so the long ones start early
     struct Item {
         int32_t cost;
-        uint32_t packed;
+        ragc::AttnItem it;
     };
     auto build_items = [&](int rows_per_item, std::vector<Item>& items) -> int {
         items.clear();
@@ -188,7 +190,8 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
             const int64_t tiles = (rows + rows_per_item - 1) / rows_per_item;
             if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
             for (int t = 0; t < (int)tiles; ++t)
-                items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t, rows_per_item), (uint32_t)r << 16 | (uint32_t)t});
+                items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t, rows_per_item),
+                                 ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
         }
         return RAGC_OK;
     };
@@ -204,9 +207,9 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
         if (int rc = build_items(ragc::attn_bf16_rows_per_item(variant), items)) return rc;
     std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.cost > y.cost; });
     for (size_t i = 0; i < items.size(); i += ragc::kAttnMaxItems) {
-        ragc::AttnWorkList wl;
+        ragc::AttnWorkList wl{};
         wl.n = (int32_t)std::min<size_t>(ragc::kAttnMaxItems, items.size() - i);
-        for (int j = 0; j < wl.n; ++j) wl.item[j] = items[i + j].packed;
+        for (int j = 0; j < wl.n; ++j) wl.item[j] = items[i + j].it;
         const hipError_t e = ragc::launch_attn_bf16(a, wl, variant, s);
         if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
     }

@@ -45,10 +45,19 @@ hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 // them in the kernel argument buffer (no device staging); long lists go out in
 // several launches.
 constexpr int kAttnRowsPerItem = 128;
-constexpr int kAttnMaxItems = 896;
+constexpr int kAttnMaxItems = 224;
+// One work item carries the request's lengths, so a workgroup needs no memory round trip
+// before it can look up its first block ids.
+struct AttnItem {
+    uint32_t req_tile;   // request << 16 | row tile
+    int32_t prefix_len;
+    int32_t new_len;
+    int32_t new_start;
+};
 struct AttnWorkList {
     int32_t n;
-    uint32_t item[kAttnMaxItems];  // request << 16 | row tile
+    int32_t pad[3];
+    AttnItem item[kAttnMaxItems];
 };
 enum AttnVariant {
     kAttnVariantOneGroup = 0,   // 4 waves per workgroup, two workgroups per CU

@@ -35,12 +35,19 @@ class DeviceWorkload:
     """A Workload resident on the GPU: pool planes (poison everywhere except the
     cached blocks), Q / fresh K,V, tables, and the ragc structs pointing at them."""
 
-    def __init__(self, w: Workload, device="cuda", resident_host_blocks: bool = True, with_host_table: bool = True):
+    def __init__(self, w: Workload, device="cuda", resident_host_blocks: bool = True, with_host_table: bool = True,
+                 pool=None):
+        """`pool` = (pool_k, pool_v) of another DeviceWorkload with the same shape: this workload's
+        blocks are placed into it (the placements must be disjoint) instead of a fresh pool."""
         self.w = w
         self.device = device
         td = torch_dtype(w.dtype)
-        self.pool_k = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
-        self.pool_v = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
+        if pool is None:
+            self.pool_k = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
+            self.pool_v = torch.full(w.pool_shape(), float("nan"), dtype=td, device=device)
+        else:
+            self.pool_k, self.pool_v = pool
+            assert tuple(self.pool_k.shape) == tuple(w.pool_shape())
         ids = w.used_block_ids
         uk, uv = w.used_k, w.used_v
         if not resident_host_blocks and w.host_dev_blocks.size:
@@ -56,15 +63,17 @@ class DeviceWorkload:
         self.out = torch.full(tuple(w.q.shape), float("nan"), dtype=td, device=device)
         self.h_prefix_len = np.ascontiguousarray(w.prefix_len, np.int32)
         self.h_new_len = np.ascontiguousarray(w.new_len, np.int32)
+        self.h_new_start = np.ascontiguousarray(w.new_start, np.int32)
         self.h_block_table = np.ascontiguousarray(w.block_table, np.int32) if with_host_table else None
         self.d_prefix_len = torch.from_numpy(self.h_prefix_len).to(device)
         self.d_new_len = torch.from_numpy(self.h_new_len).to(device)
-        self.d_new_start = torch.from_numpy(np.ascontiguousarray(w.new_start, np.int32)).to(device)
+        self.d_new_start = torch.from_numpy(self.h_new_start).to(device)
         self.d_block_table = torch.from_numpy(np.ascontiguousarray(w.block_table, np.int32)).to(device)
         self.dtype_code = B.RAGC_DTYPE_BF16 if w.dtype == "bf16" else B.RAGC_DTYPE_F32
         self.pool = B.make_pool(self.pool_k, self.pool_v, w.num_blocks, w.kv_heads, w.head_dim, self.dtype_code)
         self.batch = B.make_batch(w.num_reqs, w.table_stride, self.d_prefix_len, self.d_new_len, self.d_new_start,
-                                  self.d_block_table, self.h_prefix_len, self.h_new_len, self.h_block_table)
+                                  self.d_block_table, self.h_prefix_len, self.h_new_len, self.h_new_start,
+                                  self.h_block_table)
         self.workspace = None
         self.workspace_bytes = 0
         # host tier
@@ -89,7 +98,7 @@ class DeviceWorkload:
         hs = np.ascontiguousarray(np.concatenate([w.new_start[idx], [0]]), np.int32)
         ht = np.ascontiguousarray(w.block_table[idx], np.int32)
         dev = [torch.from_numpy(a).to(self.device) for a in (hp, hn, hs, ht)]
-        batch = B.make_batch(len(idx), w.table_stride, dev[0], dev[1], dev[2], dev[3], hp, hn, ht)
+        batch = B.make_batch(len(idx), w.table_stride, dev[0], dev[1], dev[2], dev[3], hp, hn, hs, ht)
         return batch, (hp, hn, hs, ht, dev)
 
     def attn_batch(self, batch, flags: int = 0, stream: Optional[int] = None):

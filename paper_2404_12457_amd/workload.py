@@ -262,8 +262,13 @@ def build_workload(
     host_fraction: float = 0.0,
     table_stride: Optional[int] = None,
     placement_seed: Optional[int] = None,
+    placement_skip: int = 0,
 ) -> Workload:
     """Draw tensors and place the cached prefix into paged blocks.
+
+    Block ids are taken in order from a seeded permutation of the pool; `placement_skip`
+    drops that many leading entries, so that several workloads can live in disjoint blocks
+    of one pool.
 
     Sharing rule (flat logical addressing, full-block granularity): logical block b
     of a request may be shared with every request whose document path is identical
@@ -303,7 +308,7 @@ def build_workload(
 
     # block assignment
     perm = _gen(seed if placement_seed is None else placement_seed, _T_PERM).permutation(num_blocks).astype(np.int32)
-    nxt = 0
+    nxt = int(placement_skip)
     max_blocks = max([1] + [(int(p) + int(n) + BLOCK - 1) // BLOCK for p, n in zip(w.prefix_len, w.new_len)])
     w.table_stride = int(table_stride) if table_stride is not None else max_blocks
     assert w.table_stride >= max_blocks
@@ -446,28 +451,30 @@ def _ragged_requests(seed: int, R: int, share_first: float, zipf: bool) -> List[
     return reqs
 
 
-def make_config(index: int, seed: Optional[int] = None, peaked: bool = False) -> Workload:
+def make_config(index: int, seed: Optional[int] = None, peaked: bool = False, placement_skip: int = 0,
+                placement_seed: Optional[int] = None) -> Workload:
     """The five synthetic configurations.  `peaked` multiplies Q by 8 so that the
     softmax is sharp and |O| is of the order of |V| (a tolerance of 2e-2 is then a
     meaningful fraction of the signal)."""
     seed = BASE_SEED + index if seed is None else seed
     gain = 8.0 if peaked else 1.0
     nm = CONFIG_NAMES[index] + ("-peaked" if peaked else "")
+    place = dict(placement_skip=placement_skip, placement_seed=placement_seed)
     if index == 1:
         reqs = [RequestSpec([(1, 256)], 32)]
-        return build_workload(nm, "f32", 4, 4, 64, 64, reqs, seed, 1.0, gain)
+        return build_workload(nm, "f32", 4, 4, 64, 64, reqs, seed, 1.0, gain, **place)
     if index == 2:
         reqs = [RequestSpec([(2 * r + 1, 512), (2 * r + 2, 512)], 100) for r in range(8)]
-        return build_workload(nm, "bf16", 32, 32, 128, 8192, reqs, seed, 0.5, gain)
+        return build_workload(nm, "bf16", 32, 32, 128, 8192, reqs, seed, 0.5, gain, **place)
     if index == 3:
         reqs = _ragged_requests(seed, 16, 0.2, zipf=False)
-        return build_workload(nm, "bf16", 32, 8, 128, 16384, reqs, seed, 1.0, gain)
+        return build_workload(nm, "bf16", 32, 8, 128, 16384, reqs, seed, 1.0, gain, **place)
     if index == 4:
         reqs = [RequestSpec([(8 * r + d + 1, 512) for d in range(8)], 128) for r in range(4)]
-        return build_workload(nm, "bf16", 64, 8, 128, 32768, reqs, seed, 1.0, gain)
+        return build_workload(nm, "bf16", 64, 8, 128, 32768, reqs, seed, 1.0, gain, **place)
     if index == 5:
         reqs = _ragged_requests(seed, 32, 0.0, zipf=True)
-        return build_workload(nm, "bf16", 32, 8, 128, 16384, reqs, seed, 1.0, gain, host_fraction=0.30)
+        return build_workload(nm, "bf16", 32, 8, 128, 16384, reqs, seed, 1.0, gain, host_fraction=0.30, **place)
     raise ValueError(f"no such config: {index}")
 
 

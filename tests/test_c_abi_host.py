@@ -51,8 +51,9 @@ def _pool(**kw):
 
 def _batch(p=(10,), n=(5,), stride=4, table=None, dev=A):
     hp, hn = np.asarray(p, np.int32), np.asarray(n, np.int32)
-    b = B.make_batch(len(p), stride, dev, dev, dev, dev, hp, hn, table)
-    return b, (hp, hn, table)
+    hs = np.concatenate([[0], np.cumsum(np.maximum(hn, 0))]).astype(np.int32)
+    b = B.make_batch(len(p), stride, dev, dev, dev, dev, hp, hn, hs, table)
+    return b, (hp, hn, hs, table)
 
 
 def _attn_code(pool, batch, q=A, k=A, v=A, o=A, hq=8, scale=0.1, flags=0):
@@ -86,7 +87,7 @@ def test_attention_argument_errors(lib):
     assert _attn_code(_pool(), b5) == B.RAGC_ERR_RANGE
     assert "block_table[1] = 64" in B.ragc_last_error()
     hp = np.asarray([1], np.int32)
-    b6 = B.make_batch(1, 4, A, A, A, A, None, hp, None)
+    b6 = B.make_batch(1, 4, A, A, A, A, None, hp, hp, None)
     assert _attn_code(_pool(), b6) == B.RAGC_ERR_NULL
 
 
@@ -94,7 +95,7 @@ def test_empty_work_returns_ok_without_a_device(lib):
     b, keep = _batch(p=(10, 3), n=(0, 0))
     assert B.ragc_prefill_attn(_pool(), b, None, None, None, None, 8, 0.1) == 0
     assert B.ragc_kv_append(_pool(), b, None, None) == 0
-    b0 = B.make_batch(0, 0, None, None, None, None, None, None, None)
+    b0 = B.make_batch(0, 0, None, None, None, None, None, None, None, None)
     assert B.ragc_prefill_attn(_pool(), b0, None, None, None, None, 8, 0.1) == 0
     ids = np.zeros(0, np.int32)
     assert B.ragc_kv_swap(_pool(), A, A, 2 * 16 * 128, 4, ids, ids, B.RAGC_SWAP_TO_DEVICE) == 0

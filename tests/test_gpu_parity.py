@@ -129,9 +129,10 @@ def test_requests_do_not_depend_on_batch_composition(H):
     for r in range(w.num_reqs):
         s = w.new_slice(r)
         hp, hn = dw.h_prefix_len[r : r + 1].copy(), dw.h_new_len[r : r + 1].copy()
-        ns = torch.tensor([0, int(hn[0])], dtype=torch.int32, device="cuda")
+        hs = np.array([0, int(hn[0])], np.int32)
+        ns = torch.tensor(hs, device="cuda")
         batch = B.make_batch(1, w.table_stride, dw.d_prefix_len[r : r + 1], dw.d_new_len[r : r + 1], ns,
-                             dw.d_block_table[r], hp, hn, dw.h_block_table[r])
+                             dw.d_block_table[r], hp, hn, hs, dw.h_block_table[r])
         out = torch.zeros_like(dw.q[s])
         B.ragc_prefill_attn(dw.pool, batch, dw.q[s], dw.k_new[s], dw.v_new[s], out, w.q_heads, w.softmax_scale, 0,
                             None, 0, torch.cuda.current_stream().cuda_stream)
@@ -203,8 +204,9 @@ def test_followup_request_reads_appended_blocks(H):
     v2 = W.f32_to_bf16_bits(g.standard_normal((N2, 2, 128), dtype=np.float32))
     hp, hn = np.array([P2], np.int32), np.array([N2], np.int32)
     dp, dn = torch.tensor(hp, device="cuda"), torch.tensor(hn, device="cuda")
-    ds = torch.tensor([0, N2], dtype=torch.int32, device="cuda")
-    batch = B.make_batch(1, w.table_stride, dp, dn, ds, dw.d_block_table, hp, hn, dw.h_block_table)
+    hs = np.array([0, N2], np.int32)
+    ds = torch.tensor(hs, device="cuda")
+    batch = B.make_batch(1, w.table_stride, dp, dn, ds, dw.d_block_table, hp, hn, hs, dw.h_block_table)
     dq, dk, dv = (H.to_device(x, "bf16") for x in (q2, k2, v2))
     out = torch.zeros_like(dq)
     B.ragc_prefill_attn(dw.pool, batch, dq, dk, dv, out, 8, w.softmax_scale, 0, None, 0,
@@ -228,8 +230,9 @@ def test_chunked_prefill_equals_single_call(H):
     for (p, lo, hi) in ((70, 0, 48), (118, 48, 73)):
         hp, hn = np.array([p], np.int32), np.array([hi - lo], np.int32)
         dp, dn = torch.tensor(hp, device="cuda"), torch.tensor(hn, device="cuda")
-        ds = torch.tensor([0, hi - lo], dtype=torch.int32, device="cuda")
-        batch = B.make_batch(1, w.table_stride, dp, dn, ds, two.d_block_table, hp, hn, two.h_block_table)
+        hs = np.array([0, hi - lo], np.int32)
+        ds = torch.tensor(hs, device="cuda")
+        batch = B.make_batch(1, w.table_stride, dp, dn, ds, two.d_block_table, hp, hn, hs, two.h_block_table)
         B.ragc_prefill_attn(two.pool, batch, two.q[lo:hi], two.k_new[lo:hi], two.v_new[lo:hi], out[lo:hi], 8,
                             w.softmax_scale, B.RAGC_ATTN_APPEND_FUSED, None, 0, st)
         torch.cuda.synchronize()
