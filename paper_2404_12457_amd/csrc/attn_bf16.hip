@@ -101,6 +101,17 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int wave_vis_min = P + wrow0 / G + 1;
     const int wave_vis_max = P + min(wrow0 + 31, rows_total - 1) / G + 1;
 
+    // Block ids are fetched 64 steps at a time, one per lane (entry of step blk_base+lane), and
+    // handed out with a lane read: no memory load sits on the issue path of a step.  The first
+    // window is requested before Q so that both round trips overlap; it also covers the blocks of
+    // this item's new tokens, which warms the table lines the fused append reads at the end.
+    const int nblk_item = (kv_limit + 15) >> 4;
+    int blk_base = 0;
+    int blk_vec;
+    {
+        const int e = (min(lane * NG + grp, ntiles - 1) * TN >> 4) + wq;
+        blk_vec = e < nblk_item ? table[e] : 0;
+    }
     bf16x8 qreg[KSTEPS];
     {
         const __bf16* qp = q + ((long long)(s0 + my_tok) * Hq + my_head) * D + hf * 8;
@@ -108,8 +119,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int ks = 0; ks < KSTEPS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
     // Every ordinary load above completes here, before the DMA ring starts counting.  The
-    // empty asm statements make the compiler itself wait for the Q registers now; otherwise it
+    // empty asm statements make the compiler itself wait for these registers now; otherwise it
     // would place its vmcnt waits at their first use inside the loop and drain the ring there.
+    asm volatile("" ::"v"(blk_vec));
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) asm volatile("" ::"v"(qreg[ks]));
     wait_vmcnt<0>();
@@ -125,15 +137,12 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         pool_loff[c] = (row16 * D + chunk * 8) * 2;
         new_loff[c] = (row16 * Hkv * D + chunk * 8) * 2;
     }
-    // Block ids are fetched 64 steps at a time, one per lane (entry of step blk_base+lane),
-    // and handed out with a lane read: no memory load sits on the issue path of a step.
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    int blk_vec = 0, blk_base = -64;
     auto issue = [&](int step) {
         if (step - blk_base >= 64) {
             blk_base = step;
             const int e = (min((step + lane) * NG + grp, ntiles - 1) * TN >> 4) + wq;
-            blk_vec = (e << 4) < P ? table[e] : 0;
+            blk_vec = e < nblk_item ? table[e] : 0;
             asm volatile("" ::"v"(blk_vec));  // the compiler's wait for this load stays inside the branch
         }
         const int tg = min(step * NG + grp, ntiles - 1);  // a group without a tile re-reads the last one (same count of loads)
