@@ -138,7 +138,26 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         new_loff[c] = (row16 * Hkv * D + chunk * 8) * 2;
     }
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    auto issue = [&](int step) {
+    // The copy of one step is prepared (addresses) right after the barrier and its DMA
+    // instructions are then slipped between the MFMAs of S^T = K.Q^T, where their issue cost
+    // hides under the matrix pipe; `flush` issues whatever is still pending at once.
+    int pend = 0;              // 1: a fast-path copy (uniform base + per-lane constant) waits to be issued
+    bool pend_fresh = false;   // source is the run of fresh rows, else one pool block
+    uint64_t pend_kb = 0, pend_vb = 0;
+    uint32_t pend_dst = 0;
+    auto emit = [&](int c) {
+        const uint32_t lo = pend_fresh ? new_loff[c] : pool_loff[c];
+        dma_16B_per_lane(pend_kb, lo, pend_dst + RPI * c * ROWB);
+        dma_16B_per_lane(pend_vb, lo, pend_dst + RPI * c * ROWB + PLANEB);
+    };
+    auto flush = [&]() {
+        if (pend) {
+#pragma unroll
+            for (int c = 0; c < IPB; ++c) emit(c);
+            pend = 0;
+        }
+    };
+    auto prepare = [&](int step) {
         if (step - blk_base >= 64) {
             blk_base = step;
             const int e = (min((step + lane) * NG + grp, ntiles - 1) * TN >> 4) + wq;
@@ -152,26 +171,22 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         if (kbase + 16 <= P) {
             // the whole block is cached: one pool block, uniform base + per-lane constant
             const long long boff = ((long long)blk * a.b.block_stride + (long long)g * kBlock * D) * 2;
-            const uint64_t kb = uniform_u64(reinterpret_cast<const char*>(pool_k) + boff);
-            const uint64_t vb = uniform_u64(reinterpret_cast<const char*>(pool_v) + boff);
-#pragma unroll
-            for (int c = 0; c < IPB; ++c) {
-                dma_16B_per_lane(kb, pool_loff[c], dst + RPI * c * ROWB);
-                dma_16B_per_lane(vb, pool_loff[c], dst + RPI * c * ROWB + PLANEB);
-            }
+            pend_kb = uniform_u64(reinterpret_cast<const char*>(pool_k) + boff);
+            pend_vb = uniform_u64(reinterpret_cast<const char*>(pool_v) + boff);
+            pend_dst = dst;
+            pend_fresh = false;
+            pend = 1;
         } else if (kbase >= P && kbase + 16 <= kv_limit) {
             // 16 fresh rows, all inside the horizon
             const long long boff = (((long long)(s0 + kbase - P)) * Hkv + g) * D * 2;
-            const uint64_t kb = uniform_u64(reinterpret_cast<const char*>(k_new) + boff);
-            const uint64_t vb = uniform_u64(reinterpret_cast<const char*>(v_new) + boff);
-#pragma unroll
-            for (int c = 0; c < IPB; ++c) {
-                dma_16B_per_lane(kb, new_loff[c], dst + RPI * c * ROWB);
-                dma_16B_per_lane(vb, new_loff[c], dst + RPI * c * ROWB + PLANEB);
-            }
+            pend_kb = uniform_u64(reinterpret_cast<const char*>(k_new) + boff);
+            pend_vb = uniform_u64(reinterpret_cast<const char*>(v_new) + boff);
+            pend_dst = dst;
+            pend_fresh = true;
+            pend = 1;
         } else {
-            // the block straddles the prefix end or the horizon: choose the source per row;
-            // rows past the horizon re-read the last visible one (they are masked later)
+            // the block straddles the prefix end or the horizon: choose the source per row, issue
+            // now; rows past the horizon re-read the last visible one (they are masked later)
 #pragma unroll
             for (int c = 0; c < IPB; ++c) {
                 const int row16 = RPI * c + lane / CPR;
@@ -189,6 +204,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
                 dma_16B_per_lane(ksrc, dst + RPI * c * ROWB);
                 dma_16B_per_lane(vsrc, dst + RPI * c * ROWB + PLANEB);
             }
+            pend = 0;
         }
     };
 
@@ -232,11 +248,14 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         if (RING > 2 && step + RING - 2 < nsteps) wait_vmcnt<(RING - 2) * LPS>();
         else wait_vmcnt<0>();
         block_barrier();  // every wave's part is in LDS, and every wave is done with the previous step
-        if (step + RING - 1 < nsteps) issue(step + RING - 1);
+        if (step + RING - 1 < nsteps) prepare(step + RING - 1);
 
         const int tg = step * NG + grp;
         const int base = tg * TN;
-        if (!wave_active || tg >= ntiles || base >= wave_vis_max) return;
+        if (!wave_active || tg >= ntiles || base >= wave_vis_max) {
+            flush();
+            return;
+        }
         lds_char* const kst = lds0 + SLOT * STAGEB;
         lds_char* const vst = kst + PLANEB;
 
@@ -253,7 +272,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
                 const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks]);
                 sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], sacc[sub], 0, 0, 0);
             }
+            if (ks < IPB && pend) emit(ks);  // two DMA instructions in the shadow of the MFMAs just issued
         }
+        pend = 0;
         // causal frontier / end of sequence: only tiles that reach past the first row's horizon
         if (base + TN > wave_vis_min) {
 #pragma unroll
@@ -318,7 +339,10 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 
 #pragma unroll
     for (int s = 0; s < RING - 1; ++s)
-        if (s < nsteps) issue(s);
+        if (s < nsteps) {
+            prepare(s);
+            flush();
+        }
 
     for (int step0 = 0; step0 < nsteps; step0 += RING) {
         do_step(step0, std::integral_constant<int, 0>{});
