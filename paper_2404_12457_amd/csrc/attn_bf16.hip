@@ -265,13 +265,24 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int i = 0; i < 16; ++i) sacc[sub][i] = 0.f;
+        // K operands are read two k-steps ahead of the MFMAs that consume them (LDS latency is
+        // about four MFMAs long)
+        bf16x8 kbuf[3][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+                kbuf[ks][sub] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks]);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
+            if (ks + 2 < KSTEPS) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks]);
-                sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[ks], sacc[sub], 0, 0, 0);
+                for (int sub = 0; sub < 2; ++sub)
+                    kbuf[(ks + 2) % 3][sub] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks + 2]);
             }
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+                sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kbuf[ks % 3][sub], qreg[ks], sacc[sub], 0, 0, 0);
             if (ks < IPB && pend) emit(ks);  // two DMA instructions in the shadow of the MFMAs just issued
         }
         pend = 0;

@@ -303,3 +303,24 @@ def test_empty_batches_are_no_ops(H):
     dw.append()
     torch.cuda.synchronize()
     assert torch.equal(_bits(dw.pool_k), before)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+def test_every_kernel_variant_matches_oracle(H, variant, monkeypatch):
+    """The library picks a kernel variant from the batch shape; force each one
+    (RAGC_ATTN_VARIANT) on a ragged GQA batch and on a long-prefix MHA request."""
+    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
+    w = W.make_small("bf16", 8, 2, 128, [(0, 17), (37, 20), (64, 1), (100, 133), (15, 0), (300, 250), (1030, 70)], seed=7001)
+    dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    pk, pv = w.pool_image()
+    OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
+    assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
+    assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
+    _check_all(H, W.make_small("bf16", 4, 4, 64, [(700, 100), (5, 260)], seed=7002, q_gain=6.0))
+
+
+def test_many_work_items_take_several_launches(H):
+    """More (request, row tile) items than fit one kernel-argument work list."""
+    lens = [(16 + (i % 5) * 16, 3 + (i % 7)) for i in range(300)]
+    w = W.make_small("bf16", 2, 1, 64, lens, seed=7003)
+    _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
