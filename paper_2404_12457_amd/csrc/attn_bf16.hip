@@ -457,27 +457,19 @@ void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
 
 }  // namespace
 
-int attn_bf16_item_cost(int prefix, int new_len, int group, int tile, int rows_per_item) {
+int attn_bf16_item_cost(int prefix, int new_len, int group, int tile) {
     const int rows = new_len * group;
-    const int last_row = (tile + 1) * rows_per_item < rows ? (tile + 1) * rows_per_item - 1 : rows - 1;
+    const int last_row = (tile + 1) * TM < rows ? (tile + 1) * TM - 1 : rows - 1;
     return (prefix + last_row / group + 1 + TN - 1) / TN;
 }
 
 hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s) {
     if (wl.n <= 0) return hipSuccess;
-    if (variant == kAttnVariantW64 || variant == kAttnVariantW64TwoGroups) return launch_attn_bf16_w64(a, wl, variant, s);
     const bool d64 = a.b.head_dim == 64;
-    switch (variant) {
-        case kAttnVariantTwoGroups:
-            d64 ? launch_one<64, 2, 2>(a, wl, s) : launch_one<128, 2, 2>(a, wl, s);
-            break;
-        case kAttnVariantDeepRing:
-            d64 ? launch_one<64, 1, 4>(a, wl, s) : launch_one<128, 1, 4>(a, wl, s);
-            break;
-        default:
-            d64 ? launch_one<64, 1, 2>(a, wl, s) : launch_one<128, 1, 2>(a, wl, s);
-            break;
-    }
+    if (variant == kAttnVariantTwoGroups)
+        d64 ? launch_one<64, 2, 2>(a, wl, s) : launch_one<128, 2, 2>(a, wl, s);
+    else
+        d64 ? launch_one<64, 1, 2>(a, wl, s) : launch_one<128, 1, 2>(a, wl, s);
     return hipGetLastError();
 }
 

@@ -182,29 +182,22 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
         int32_t cost;
         ragc::AttnItem it;
     };
-    auto build_items = [&](int rows_per_item, std::vector<Item>& items) -> int {
-        items.clear();
-        for (int r = 0; r < batch->num_reqs; ++r) {
-            const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
-            const int64_t rows = (int64_t)n * a.group;
-            const int64_t tiles = (rows + rows_per_item - 1) / rows_per_item;
-            if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
-            for (int t = 0; t < (int)tiles; ++t)
-                items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t, rows_per_item),
-                                 ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
-        }
-        return RAGC_OK;
-    };
     std::vector<Item> items;
-    // 128-row items.  With at least two work items per CU two 4-wave workgroups share a CU;
-    // otherwise one 8-wave workgroup splits the keys between two wave groups.
-    int variant = ragc::kAttnVariantOneGroup;
-    if (int rc = build_items(ragc::attn_bf16_rows_per_item(variant), items)) return rc;
-    if ((int64_t)items.size() * pool->kv_heads < 2 * (int64_t)cu_count()) variant = ragc::kAttnVariantTwoGroups;
+    for (int r = 0; r < batch->num_reqs; ++r) {
+        const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
+        const int64_t rows = (int64_t)n * a.group;
+        const int64_t tiles = (rows + ragc::kAttnRowsPerItem - 1) / ragc::kAttnRowsPerItem;
+        if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
+        for (int t = 0; t < (int)tiles; ++t)
+            items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t),
+                             ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
+    }
+    // With at least two work items per CU two 4-wave workgroups share a CU; otherwise one 8-wave
+    // workgroup splits the keys between two wave groups.  RAGC_ATTN_VARIANT overrides (tests).
+    int variant = (int64_t)items.size() * pool->kv_heads >= 2 * (int64_t)cu_count() ? ragc::kAttnVariantOneGroup
+                                                                                      : ragc::kAttnVariantTwoGroups;
     if (const char* force = std::getenv("RAGC_ATTN_VARIANT")) variant = std::atoi(force);
-    if (variant < 0 || variant > ragc::kAttnVariantW64TwoGroups) return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VARIANT %d unknown", variant);
-    if (ragc::attn_bf16_rows_per_item(variant) != ragc::attn_bf16_rows_per_item(ragc::kAttnVariantOneGroup))
-        if (int rc = build_items(ragc::attn_bf16_rows_per_item(variant), items)) return rc;
+    if (variant < 0 || variant >= ragc::kAttnVariantCount) return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VARIANT %d unknown", variant);
     std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.cost > y.cost; });
     for (size_t i = 0; i < items.size(); i += ragc::kAttnMaxItems) {
         ragc::AttnWorkList wl{};

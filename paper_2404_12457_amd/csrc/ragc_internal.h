@@ -62,16 +62,11 @@ struct AttnWorkList {
 enum AttnVariant {
     kAttnVariantOneGroup = 0,   // 4 waves per workgroup, two workgroups per CU
     kAttnVariantTwoGroups = 1,  // 8 waves per workgroup on alternating key tiles
-    kAttnVariantDeepRing = 2,   // 4 waves, four-stage ring (three tiles in flight)
-    kAttnVariantW64 = 3,          // 64 rows per wave, 256 rows per item, K/V rings of four tiles
-    kAttnVariantW64TwoGroups = 4  // 64 rows per wave, 128 rows per item, two groups on alternating key tiles
+    kAttnVariantCount = 2
 };
-// rows of one work item in a variant
-inline int attn_bf16_rows_per_item(int variant) { return variant == kAttnVariantW64 ? 256 : 128; }
-// number of 64-key tiles the work item (row tile `tile` of `rows_per_item` rows) walks
-int attn_bf16_item_cost(int prefix, int new_len, int group, int tile, int rows_per_item);
+// number of 64-key tiles the work item (row tile `tile` of kAttnRowsPerItem rows) walks
+int attn_bf16_item_cost(int prefix, int new_len, int group, int tile);
 hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s);
-hipError_t launch_attn_bf16_w64(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s);
 
 hipError_t launch_append(const PagedBatch& b, void* pool_k, void* pool_v, const void* k_new, const void* v_new,
                          int32_t total_new, int esize, hipStream_t s);

@@ -305,7 +305,7 @@ def test_empty_batches_are_no_ops(H):
     assert torch.equal(_bits(dw.pool_k), before)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [0, 1])
 def test_every_kernel_variant_matches_oracle(H, variant, monkeypatch):
     """The library picks a kernel variant from the batch shape; force each one
     (RAGC_ATTN_VARIANT) on a ragged GQA batch and on a long-prefix MHA request."""
