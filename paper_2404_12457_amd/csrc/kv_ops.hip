@@ -22,31 +22,71 @@ __device__ __forceinline__ int find_request(const int32_t* __restrict__ new_star
     return lo;
 }
 
-// One thread moves one 16-byte chunk of K and the matching chunk of V.
-// chunks per token row = kv_heads * head_dim * esize / 16.
+// Append.  A workgroup owns 16 consecutive packed rows (tokens) and a run of kv heads: 1024
+// 16-byte chunks per plane, four of K and four of V per thread, all loads issued before the
+// first store.  For one head the 16 rows land next to each other in the pool (a 16-token block
+// is contiguous per head), so a wave writes whole 1 KiB runs and the workgroup reads 16 row
+// pieces of 1 KiB or more; both sides stay within a few DRAM pages.  The rows are resolved to
+// their paged slots once per workgroup (16 threads) and shared through LDS.  Loads and stores
+// are nontemporal: nothing here is touched twice.
+constexpr int kAppendRows = 16;
+constexpr int kAppendUnroll = 4;
+constexpr int kAppendChunksPerGroup = 256 * kAppendUnroll;
+
 __global__ __launch_bounds__(256) void append_kernel(PagedBatch b, char* __restrict__ pool_k, char* __restrict__ pool_v,
                                                      const char* __restrict__ k_new, const char* __restrict__ v_new,
-                                                     int total_new, int esize) {
-    const int head_bytes = b.head_dim * esize;
-    const int chunks_per_head = head_bytes >> 4;
-    const int chunks_per_row = b.kv_heads * chunks_per_head;
-    const long long total = (long long)total_new * chunks_per_row;
+                                                     int total_new, int esize, int head_groups) {
+    __shared__ long long slot_off[kAppendRows];  // byte offset of (block, head 0, slot) of each row; -1: no such row
     const int first_row = b.new_start[0];  // a sub-batch may start anywhere in the packed arrays
-    for (long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x; c < total; c += (long long)gridDim.x * blockDim.x) {
-        const int t_rel = (int)(c / chunks_per_row);
-        const int in_row = (int)(c - (long long)t_rel * chunks_per_row);
-        const int t = first_row + t_rel;
-        const int g = in_row / chunks_per_head;
-        const int ch = in_row - g * chunks_per_head;
-        const int r = find_request(b.new_start, b.num_reqs, t);
-        const int pos = b.prefix_len[r] + (t - b.new_start[r]);
-        const int blk = b.block_table[(long long)r * b.table_stride + (pos >> 4)];
-        const long long dst = ((long long)blk * b.block_stride + ((long long)g * kBlock + (pos & 15)) * b.head_dim) * esize + (ch << 4);
-        const long long src = ((long long)first_row * chunks_per_row + c) << 4;
-        const u32x4 kk = *reinterpret_cast<const u32x4*>(k_new + src);
-        const u32x4 vv = *reinterpret_cast<const u32x4*>(v_new + src);
-        *reinterpret_cast<u32x4*>(pool_k + dst) = kk;
-        *reinterpret_cast<u32x4*>(pool_v + dst) = vv;
+    // the head group varies fastest, so workgroups that run together cover whole source rows
+    const int hg = blockIdx.x % head_groups;
+    const int t0 = (blockIdx.x / head_groups) * kAppendRows;
+    const int head_bytes = b.head_dim * esize;
+    if (threadIdx.x < kAppendRows) {
+        const int t_rel = t0 + threadIdx.x;
+        long long off = -1;
+        if (t_rel < total_new) {
+            const int t = first_row + t_rel;
+            const int r = find_request(b.new_start, b.num_reqs, t);
+            const int pos = b.prefix_len[r] + (t - b.new_start[r]);
+            const int blk = b.block_table[(long long)r * b.table_stride + (pos >> 4)];
+            off = ((long long)blk * b.block_stride + (long long)(pos & 15) * b.head_dim) * esize;
+        }
+        slot_off[threadIdx.x] = off;
+    }
+    __syncthreads();
+    // chunks per head is 8, 16 or 32 (head_dim 64 or 128, 2 or 4 bytes per element)
+    const int cph_shift = __ffs(head_bytes >> 4) - 1;
+    const int per_head_shift = cph_shift + 4;  // chunks of one head over the 16 rows
+    const int total = b.kv_heads << per_head_shift;
+    const long long row_bytes = (long long)b.kv_heads * head_bytes;
+    const long long src0 = (long long)(first_row + t0) * row_bytes;
+    const long long dst_head_stride = (long long)kBlock * head_bytes;
+    u32x4 kk[kAppendUnroll], vv[kAppendUnroll];
+    long long dst[kAppendUnroll];
+#pragma unroll
+    for (int u = 0; u < kAppendUnroll; ++u) {
+        const int idx = hg * kAppendChunksPerGroup + u * 256 + threadIdx.x;  // (head, row, chunk), chunk fastest
+        dst[u] = -1;
+        if (idx < total) {
+            const int g = idx >> per_head_shift;
+            const int row = (idx >> cph_shift) & (kAppendRows - 1);
+            const int ch = idx & ((1 << cph_shift) - 1);
+            const long long so = slot_off[row];
+            if (so >= 0) {
+                dst[u] = so + g * dst_head_stride + (ch << 4);
+                const long long src = src0 + row * row_bytes + (long long)g * head_bytes + (ch << 4);
+                kk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k_new + src));
+                vv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v_new + src));
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kAppendUnroll; ++u) {
+        if (dst[u] >= 0) {
+            __builtin_nontemporal_store(kk[u], reinterpret_cast<u32x4*>(pool_k + dst[u]));
+            __builtin_nontemporal_store(vv[u], reinterpret_cast<u32x4*>(pool_v + dst[u]));
+        }
     }
 }
 
@@ -110,11 +150,13 @@ inline int grid_for(long long items, int per_block, int cap) {
 hipError_t launch_append(const PagedBatch& b, void* pool_k, void* pool_v, const void* k_new, const void* v_new,
                          int32_t total_new, int esize, hipStream_t s) {
     if (total_new <= 0) return hipSuccess;
-    const long long chunks = (long long)total_new * b.kv_heads * ((b.head_dim * esize) >> 4);
-    const int grid = grid_for(chunks, 256, 256 * 64);
-    hipLaunchKernelGGL(append_kernel, dim3(grid), dim3(256), 0, s, b, static_cast<char*>(pool_k),
+    const int chunks_per_group_of_rows = kAppendRows * b.kv_heads * ((b.head_dim * esize) >> 4);
+    const int head_groups = (chunks_per_group_of_rows + kAppendChunksPerGroup - 1) / kAppendChunksPerGroup;
+    const long long grid = (long long)((total_new + kAppendRows - 1) / kAppendRows) * head_groups;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)grid), dim3(256), 0, s, b, static_cast<char*>(pool_k),
                        static_cast<char*>(pool_v), static_cast<const char*>(k_new), static_cast<const char*>(v_new),
-                       total_new, esize);
+                       total_new, esize, head_groups);
     return hipGetLastError();
 }
 

@@ -161,7 +161,8 @@ def test_future_tokens_do_not_change_a_row(H):
     assert np.array_equal(pert[:60], base[:60]) and not np.array_equal(pert[60:], base[60:])
 
 
-@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 8, 2, 128), ("f32", 4, 4, 64), ("bf16", 4, 4, 64)])
+@pytest.mark.parametrize("dtype,hq,hkv,d", [("bf16", 8, 2, 128), ("f32", 4, 4, 64), ("bf16", 4, 4, 64),
+                                            ("f32", 6, 3, 128), ("bf16", 10, 5, 128), ("bf16", 3, 3, 64)])
 def test_append_fused_standalone_and_oracle_agree_bytewise(H, dtype, hq, hkv, d):
     lens = [(0, 5), (37, 20), (64, 1), (100, 133), (15, 0), (250, 47)]
     w = W.make_small(dtype, hq, hkv, d, lens, seed=61)
