@@ -404,9 +404,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     }
 
     // ---- merge the wave groups through LDS (the DMA ring is idle now)
+    constexpr int WSTRIDE = (DT * 16 + 2) * 64;  // floats per wave in the merge area
     if (NG > 1) {
         float* xf = reinterpret_cast<float*>(smem);
-        constexpr int WSTRIDE = (DT * 16 + 2) * 64;  // floats per wave
         block_barrier();
         if (grp == 1) {
             float* dst = xf + wq * WSTRIDE + lane;
@@ -430,23 +430,42 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[dt][i] = oacc[dt][i] * s0f + src[(dt * 16 + i) * 64] * s1f;
         }
+    } else {
+        block_barrier();  // every wave is done with the ring: its memory is reused below
     }
 
-    // ---- normalise and store: lane holds 4 consecutive d per (dt, i/4)
+    // ---- normalise and store.  A lane holds 4 consecutive d of ONE row per (dt, i/4), so a direct
+    // store would touch 32 rows with 16 bytes each per instruction; instead the wave turns its 32
+    // rows around in a private LDS patch (rows padded by 16 bytes) and stores whole rows, 16 bytes
+    // per lane.  With two groups the patch is the wave's own merge area, which only it reads.
     if (!wave_active) return;
+    constexpr int OROWB = ROWB + 16;
+    static_assert(32 * OROWB <= WSTRIDE * 4, "output patch fits the merge area");
+    lds_char* const patch = lds0 + wq * (NG > 1 ? WSTRIDE * 4 : 32 * OROWB);
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.f / l_tot;
-    if (wrow0 + l32 < rows_total) {
-        __bf16* op = static_cast<__bf16*>(a.out) + ((long long)(s0 + my_tok) * Hq + my_head) * D;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                bf16x4 o4;
+        for (int i4 = 0; i4 < 4; ++i4) {
+            bf16x4 o4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][i4 * 4 + e] * inv);
-                *reinterpret_cast<bf16x4*>(op + dt * 32 + i4 * 8 + hf * 4) = o4;
-            }
+            for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][i4 * 4 + e] * inv);
+            *reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(patch + l32 * OROWB + (dt * 32 + i4 * 8 + hf * 4) * 2) = o4;
+        }
+    // lanes now read what other lanes of the same wave wrote: LDS operations of a wave complete in order
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __bf16* const outp = static_cast<__bf16*>(a.out);
+#pragma unroll
+    for (int p = 0; p < 32 / RPI; ++p) {
+        const int rr = p * RPI + lane / CPR;
+        const int row = wrow0 + rr;
+        const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(patch + rr * OROWB + (lane % CPR) * 16);
+        if (row < rows_total) {
+            const int tok = row / G;
+            const int head = g * G + (row - tok * G);
+            *reinterpret_cast<u32x4*>(outp + ((long long)(s0 + tok) * Hq + head) * D + (lane % CPR) * 8) = v;
+        }
     }
 }
 
