@@ -68,6 +68,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int r = it.req_tile >> 16, tile = it.req_tile & 0xffff;
 
     const int G = a.group;
+    // x / G for 0 <= x < 2^26 / G without an integer division (the host supplies ceil(2^32 / G), 0 for G = 1)
+    const uint32_t g_magic = a.group_magic;
+    auto div_g = [&](int x) { return g_magic ? (int)__umulhi((uint32_t)x, g_magic) : x; };
     const int N = it.new_len;
     const int rows_total = N * G;
     const int row0 = tile * TM;
@@ -87,19 +90,19 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int32_t* __restrict__ table = a.b.block_table + (long long)r * a.b.table_stride;
 
     const int last_row = min(row0 + TM, rows_total) - 1;
-    const int kv_limit = P + last_row / G + 1;  // keys [0, kv_limit) are visible to some row of the item
+    const int kv_limit = P + div_g(last_row) + 1;  // keys [0, kv_limit) are visible to some row of the item
     const int ntiles = (kv_limit + TN - 1) / TN;
     const int nsteps = (ntiles + NG - 1) / NG;  // group `grp` takes tile step*NG + grp
 
     // ---- this lane's query row
     const int wrow0 = row0 + wq * 32;
     const int my_row = min(wrow0 + l32, rows_total - 1);  // rows past the end repeat the last one
-    const int my_tok = my_row / G;
+    const int my_tok = div_g(my_row);
     const int my_head = g * G + (my_row - my_tok * G);
     const int my_vis = P + my_tok + 1;  // keys [0, my_vis) are visible to this row
     const bool wave_active = wrow0 < rows_total;
-    const int wave_vis_min = P + wrow0 / G + 1;
-    const int wave_vis_max = P + min(wrow0 + 31, rows_total - 1) / G + 1;
+    const int wave_vis_min = P + div_g(wrow0) + 1;
+    const int wave_vis_max = P + div_g(min(wrow0 + 31, rows_total - 1)) + 1;
 
     // Block ids are fetched 64 steps at a time, one per lane (entry of step blk_base+lane), and
     // handed out with a lane read: no memory load sits on the issue path of a step.  The first
@@ -368,8 +371,8 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     // because the loop has just read them as keys).  This work item owns the tokens whose first
     // row (head 0 of the group) it holds; 16-byte chunks, four per thread in flight.
     if (a.fused_append) {
-        const int tok_lo = (row0 + G - 1) / G;
-        const int tok_hi = min(N - 1, (row0 + TM - 1) / G);
+        const int tok_lo = div_g(row0 + G - 1);
+        const int tok_hi = min(N - 1, div_g(row0 + TM - 1));
         __bf16* wk = static_cast<__bf16*>(a.pool_k_w);
         __bf16* wv = static_cast<__bf16*>(a.pool_v_w);
         const int n = (tok_hi - tok_lo + 1) * CPR;
@@ -404,31 +407,38 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     }
 
     // ---- merge the wave groups through LDS (the DMA ring is idle now)
-    constexpr int WSTRIDE = (DT * 16 + 2) * 64;  // floats per wave in the merge area
+    constexpr int WSTRIDE = (DT * 16 + 4) * 64;  // floats per wave in the merge area: [DT*4 + 1 chunks][64 lanes][4]
     if (NG > 1) {
-        float* xf = reinterpret_cast<float*>(smem);
+        typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+        lds_f32x4* const xw = reinterpret_cast<lds_f32x4*>(lds0 + wq * (WSTRIDE * 4)) + lane;
         block_barrier();
         if (grp == 1) {
-            float* dst = xf + wq * WSTRIDE + lane;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(dt * 16 + i) * 64] = oacc[dt][i];
-            dst[DT * 16 * 64] = m_run;
-            dst[(DT * 16 + 1) * 64] = l_run;
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 v = {oacc[dt][i4 * 4], oacc[dt][i4 * 4 + 1], oacc[dt][i4 * 4 + 2], oacc[dt][i4 * 4 + 3]};
+                    xw[(dt * 4 + i4) * 64] = v;
+                }
+            const f32x4 ml = {m_run, l_run, 0.f, 0.f};
+            xw[DT * 4 * 64] = ml;
         }
         block_barrier();
         if (grp == 1) return;
         if (wave_active) {
-            const float* src = xf + wq * WSTRIDE + lane;
-            const float m1 = src[DT * 16 * 64], l1 = src[(DT * 16 + 1) * 64];
+            const f32x4 ml = xw[DT * 4 * 64];
+            const float m1 = ml[0], l1 = ml[1];
             const float m = fmaxf(m_run, m1);  // group 0 always saw key 0: finite
             const float s0f = __builtin_amdgcn_exp2f(m_run - m), s1f = __builtin_amdgcn_exp2f(m1 - m);
             l_run = l_run * s0f + l1 * s1f;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[dt][i] = oacc[dt][i] * s0f + src[(dt * 16 + i) * 64] * s1f;
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 v = xw[(dt * 4 + i4) * 64];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) oacc[dt][i4 * 4 + e] = oacc[dt][i4 * 4 + e] * s0f + v[e] * s1f;
+                }
         }
     } else {
         block_barrier();  // every wave is done with the ring: its memory is reused below
@@ -462,7 +472,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         const int row = wrow0 + rr;
         const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(patch + rr * OROWB + (lane % CPR) * 16);
         if (row < rows_total) {
-            const int tok = row / G;
+            const int tok = div_g(row);
             const int head = g * G + (row - tok * G);
             *reinterpret_cast<u32x4*>(outp + ((long long)(s0 + tok) * Hq + head) * D + (lane % CPR) * 8) = v;
         }

@@ -167,6 +167,7 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     a.pool_v_w = pool->v;
     a.q_heads = q_heads;
     a.group = q_heads / pool->kv_heads;
+    a.group_magic = a.group == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + a.group - 1) / a.group);
     a.scale_log2e = softmax_scale * 1.44269504088896340736f;
     a.fused_append = (flags & RAGC_ATTN_APPEND_FUSED) ? 1 : 0;
     a.max_new = info.max_new;

@@ -33,6 +33,7 @@ struct AttnLaunch {
     void* pool_v_w;
     int32_t q_heads;
     int32_t group;      // q_heads / kv_heads
+    uint32_t group_magic;  // ceil(2^32 / group), 0 for group 1: row / group by one multiply in the kernels
     float scale_log2e;  // softmax_scale * log2(e)
     int32_t fused_append;
     int32_t max_new;  // max over requests of new_len (host-side)
