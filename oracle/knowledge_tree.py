@@ -161,6 +161,20 @@ class KnowledgeTree:
         for tier in (GPU, HOST):
             node.Priority[tier] = self.Clock[tier] + node.AvgCost * node.Frequency
 
+    def _freeable(self, n: Node) -> Tuple[bool, int]:
+        """(can n itself be evicted from the GPU eventually, blocks that evictions below and at n can free):
+        a node can go once every child in GPU memory has gone, and nodes of requests in flight stay."""
+        ok = n.where == GPU and n.pins == 0
+        blocks = 0
+        for c in n.children.values():
+            if c.where == GPU:
+                c_ok, c_blocks = self._freeable(c)
+                blocks += c_blocks
+                ok = ok and c_ok
+        if ok:
+            blocks += n.n_owned
+        return ok, blocks
+
     # ---- host tier: make `required` slots free by dropping host-only leaves
     def _evict_in_host(self, required: int, gone: List[int]) -> bool:
         while len(self.free_host) < required:
@@ -177,8 +191,7 @@ class KnowledgeTree:
         freed = 0
         while freed < required_size:
             S = self._gpu_leaves()
-            if not S:
-                raise NoRoom()
+            assert S, "begin() has checked that enough can be freed"
             n = min(S, key=lambda x: (x.Priority[GPU], x.ident))
             self.Clock[GPU] = max(self.Clock[GPU], n.Priority[GPU])
             plan.evicted_gpu.append(n.ident)
@@ -224,13 +237,12 @@ class KnowledgeTree:
         cacheable = docs_total // BLOCK
         to_swap_in = [n for n in path if n.where == HOST]
         need = sum(n.n_owned for n in to_swap_in) + (blocks_total - alpha // BLOCK)
-        try:
-            if need > len(self.free_dev):
-                self._evict_in_gpu(need - len(self.free_dev), plan)
-        except NoRoom:
+        if need > len(self.free_dev) + self._freeable(self.root)[1]:
             for n in path:
                 n.pins -= 1
-            raise
+            raise NoRoom()  # nothing has been changed
+        if need > len(self.free_dev):
+            self._evict_in_gpu(need - len(self.free_dev), plan)
         # swap-in of matched nodes that live in host memory (their host copy stays valid)
         for n in to_swap_in:
             n.dev_blocks = [self.free_dev.pop() for _ in range(n.n_owned)]
@@ -271,6 +283,11 @@ class KnowledgeTree:
         for n in nodes:
             n.pins -= 1
         self.free_dev.extend(private)
+
+    def reset_frequencies(self) -> None:
+        """Frequency counts retrievals within a time window (Sec. 5.1): start a new window."""
+        for n in self._all_nodes():
+            n.Frequency = 0
 
     # ---- views for tests
     def find(self, doc_path: Sequence[int]) -> Optional[Node]:

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libragc.so")
-SOURCES = ["ragc_api.cpp", "kv_ops.hip", "attn_f32.hip", "attn_bf16.hip"]
+SOURCES = ["ragc_api.cpp", "ragc_ctl.cpp", "kv_ops.hip", "attn_f32.hip", "attn_bf16.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
     # packed fp32 math is kept off on this target (see the build notes)

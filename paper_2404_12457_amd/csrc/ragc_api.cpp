@@ -13,16 +13,22 @@
 #include "ragc_internal.h"
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
-int fail(int code, const char* fmt, ...) {
+namespace ragc {
+int set_error(int code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return code;
 }
+}  // namespace ragc
+
+namespace {
+
+int (&fail)(int, const char*, ...) = ragc::set_error;
 
 int esize_of(int32_t dtype) { return dtype == RAGC_DTYPE_BF16 ? 2 : dtype == RAGC_DTYPE_F32 ? 4 : 0; }
 

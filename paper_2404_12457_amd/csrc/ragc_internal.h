@@ -8,6 +8,9 @@ namespace ragc {
 
 constexpr int kBlock = 16;  // tokens per paged block
 
+// Records the text that ragc_last_error() returns on this thread; returns `code`.
+int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // Everything a device kernel needs to find the K/V of a batch.
 struct PagedBatch {
     const void* pool_k;

@@ -21,11 +21,14 @@ def lib():
     return B.load()
 
 
-def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "ragc.h")).read()
+@pytest.mark.parametrize("header_name,exports", [("ragc.h", "binding"), ("ragc_ctl.h", "ctl")])
+def test_every_declared_symbol_is_exported(lib, header_name, exports):
+    from paper_2404_12457_amd import ctl
+
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(ragc_[a-z_0-9]+)\s*\(", header))
-    assert names == set(B.EXPORTS)
+    assert names == set(B.EXPORTS if exports == "binding" else ctl.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 

@@ -1,0 +1,142 @@
+"""The C++ controller (include/ragc_ctl.h) against the Python oracle on seeded request traces:
+every decision is compared (matched documents, alpha, beta, block tables, swap lists, eviction
+order in both tiers, clocks, statistics, per-node frequency / cost / priorities), and the
+refusals come at the same requests.  CPU only: the controller makes no GPU call."""
+import random
+
+import numpy as np
+import pytest
+
+from oracle import knowledge_tree as KT
+from paper_2404_12457_amd import binding as B
+from paper_2404_12457_amd import ctl as C
+
+ALPHAS = [0.0, 256.0, 1024.0, 4096.0]
+BETAS = [1.0, 64.0, 256.0, 1024.0, 4096.0]
+
+
+def _grid(f):
+    return [[f(a, b) for b in BETAS] for a in ALPHAS]
+
+
+def _pair(gpu_blocks, host_slots, f):
+    t = _grid(f)
+    return KT.KnowledgeTree(gpu_blocks, host_slots, ALPHAS, BETAS, t), C.Tree(gpu_blocks, host_slots, C.CostGrid(ALPHAS, BETAS, t))
+
+
+def _same_plan(po: KT.Plan, pc: C.Plan):
+    assert (po.request_id, po.matched_docs, po.alpha, po.beta) == (pc.request_id, pc.matched_docs, pc.alpha, pc.beta)
+    assert po.block_table == pc.block_table.tolist()
+    assert po.swap_out == list(zip(pc.swap_out_dev.tolist(), pc.swap_out_slot.tolist()))
+    assert po.swap_in == list(zip(pc.swap_in_dev.tolist(), pc.swap_in_slot.tolist()))
+    assert po.evicted_gpu == pc.evicted_gpu.tolist() and po.evicted_host == pc.evicted_host.tolist()
+
+
+def _same_node(no: KT.Node, nc):
+    if no is None:
+        assert nc is None
+        return
+    assert nc is not None
+    assert (no.ident, no.where == KT.GPU, no.host_valid, no.length, no.n_owned, no.pins, no.Frequency, no.numComputed) == \
+           (nc.id, bool(nc.in_gpu), bool(nc.host_valid), nc.length, nc.n_owned, nc.pins, nc.frequency, nc.num_computed)
+    assert nc.avg_cost == pytest.approx(no.AvgCost, rel=1e-13)
+    assert nc.priority_gpu == pytest.approx(no.Priority[KT.GPU], rel=1e-13)
+    assert nc.priority_host == pytest.approx(no.Priority[KT.HOST], rel=1e-13)
+
+
+def _same_stats(to: KT.KnowledgeTree, tc: C.Tree):
+    s = tc.stats()
+    nodes = [n for n in to._all_nodes() if n is not to.root]
+    assert (s.nodes, s.nodes_in_gpu) == (len(nodes), sum(n.where == KT.GPU for n in nodes))
+    assert (s.free_gpu_blocks, s.free_host_slots) == (len(to.free_dev), len(to.free_host))
+    assert (s.docs_requested, s.docs_hit) == (to.docs_requested, to.docs_hit)
+    assert (s.blocks_swapped_out, s.blocks_swapped_in, s.zero_copy_evictions) == \
+           (to.blocks_swapped_out, to.blocks_swapped_in, to.zero_copy_evictions)
+    assert s.clock_gpu == pytest.approx(to.Clock[KT.GPU], rel=1e-13) and s.clock_host == pytest.approx(to.Clock[KT.HOST], rel=1e-13)
+
+
+@pytest.mark.parametrize("gpu_blocks,host_slots,ndocs,seed", [
+    (48, 96, 40, 1),      # both tiers under pressure
+    (24, 12, 25, 2),      # host tier smaller than the GPU tier: first copies often fail
+    (400, 0, 60, 3),      # no host tier at all
+    (64, 4096, 200, 4),   # roomy host tier: swap-out-only-once dominates
+    (4096, 64, 30, 5),    # everything fits in GPU memory
+])
+def test_traces_agree_decision_by_decision(gpu_blocks, host_slots, ndocs, seed):
+    rng = random.Random(seed)
+    f = lambda a, b: 3.0 + 0.004 * a + 0.11 * b + 2.5e-5 * a * b
+    to, tc = _pair(gpu_blocks, host_slots, f)
+    lens = {d: rng.choice([rng.randrange(1, 16), rng.randrange(16, 200), 16 * rng.randrange(1, 9)]) for d in range(ndocs)}
+    live, refused, served = [], 0, 0
+    for step in range(1500):
+        if live and (len(live) >= 3 or rng.random() < 0.5):
+            rid = live.pop(rng.randrange(len(live)))
+            to.end(rid)
+            tc.end(rid)
+        docs = list(dict.fromkeys(min(int(rng.paretovariate(1.05)) - 1, ndocs - 1) for _ in range(rng.randrange(0, 5))))
+        q = rng.randrange(0 if docs else 1, 50)
+        dl = [lens[d] for d in docs]
+        try:
+            po = to.begin(docs, dl, q)
+        except KT.NoRoom:
+            with pytest.raises(B.RagcError) as e:
+                tc.begin(docs, dl, q)
+            assert e.value.code == B.RAGC_ERR_RANGE
+            refused += 1
+            _same_stats(to, tc)
+            continue
+        pc = tc.begin(docs, dl, q)
+        _same_plan(po, pc)
+        live.append(po.request_id)
+        served += 1
+        for k in range(1, len(docs) + 1):
+            _same_node(to.find(docs[:k]), tc.find(docs[:k]))
+        if step % 50 == 0:
+            _same_stats(to, tc)
+            to.check_invariants()
+        if step == 700:
+            to.reset_frequencies()
+            tc.reset_frequencies()
+    _same_stats(to, tc)
+    assert served > 300
+    if gpu_blocks < 100:
+        assert refused > 0 or to.zero_copy_evictions + to.blocks_swapped_out > 0
+
+
+def test_cost_interp_matches_the_oracle_inside_and_outside_the_grid():
+    rng = np.random.default_rng(9)
+    t = rng.uniform(1.0, 90.0, (len(ALPHAS), len(BETAS)))
+    g = C.CostGrid(ALPHAS, BETAS, t)
+    for _ in range(500):
+        a, b = rng.uniform(-300, 6000), rng.uniform(-10, 6000)
+        assert C.ragc_cost_interp(g, a, b) == pytest.approx(KT.bilinear(ALPHAS, BETAS, t.tolist(), a, b), rel=1e-13, abs=1e-12)
+    for i, a in enumerate(ALPHAS):
+        for j, b in enumerate(BETAS):
+            assert C.ragc_cost_interp(g, a, b) == pytest.approx(t[i, j], rel=1e-15)
+
+
+def test_controller_rejects_bad_arguments_without_changing_anything():
+    tc = C.Tree(8, 8, C.CostGrid(ALPHAS, BETAS, _grid(lambda a, b: b)))
+    with pytest.raises(B.RagcError) as e:
+        tc.begin([1, 1], [16, 16], 4)  # the same document twice
+    assert e.value.code == B.RAGC_ERR_SHAPE
+    with pytest.raises(B.RagcError) as e:
+        tc.begin([1], [0], 4)
+    assert e.value.code == B.RAGC_ERR_RANGE
+    with pytest.raises(B.RagcError) as e:
+        tc.begin([], [], 0)  # no tokens at all
+    assert e.value.code == B.RAGC_ERR_RANGE
+    with pytest.raises(B.RagcError) as e:
+        tc.begin([1], [16 * 9], 0)  # larger than the GPU tier
+    assert e.value.code == B.RAGC_ERR_RANGE
+    p = tc.begin([1], [32], 4)
+    with pytest.raises(B.RagcError) as e:
+        tc.begin([1], [48], 4)  # a document id always comes with the same length
+    assert e.value.code == B.RAGC_ERR_SHAPE
+    with pytest.raises(B.RagcError):
+        tc.end(p.request_id + 7)
+    tc.end(p.request_id)
+    s = tc.stats()
+    assert (s.nodes, s.free_gpu_blocks, s.docs_requested) == (1, 6, 1)
+    with pytest.raises(B.RagcError):
+        C.Tree(8, 8, C.CostGrid([0.0, 0.0], BETAS, np.zeros((2, len(BETAS)))))  # alpha not increasing
