@@ -25,6 +25,8 @@
  *  - Swap out only once (Sec. 5.1): the first GPU eviction of a node copies its blocks to host
  *    slots, which the node keeps while it is in the tree; later GPU evictions copy nothing.
  *    When the host tier cannot make room for a first copy the node and its subtree are freed.
+ *    A first copy is struck from the request's list again when, later in the same request, the
+ *    host tier drops that node: its slot may already be promised to another node.
  *  - Device block ids and host slot ids come from LIFO free lists that start as 0, 1, 2, ...
  *  - T(alpha, beta): bilinear interpolation in the profiled grid (Algorithm 1, interpolation
  *    steps); outside the grid the outermost cell is extended linearly.

@@ -23,7 +23,8 @@ What the paper leaves open, and the reading taken here (the C++ side documents t
 * Swap out only once: a node's blocks are copied to host slots at its first GPU eviction and
   the host copy is kept while the node is in the tree; later GPU evictions copy nothing.  If
   the host tier cannot make room for a first copy, the node and everything below it leave the
-  cache.
+  cache.  A first copy that a request asked for is struck from its list again when, later in
+  the same request, the host tier drops that node (its slot may already be promised to another).
 * Block ids come from a LIFO free list that starts as 0, 1, 2, ... (so results are
   reproducible); this order is part of what the C++ side is compared on.
 * Outside the profiled grid T is extrapolated linearly from the two nearest grid lines of
@@ -139,16 +140,21 @@ class KnowledgeTree:
         return [n for n in self._all_nodes()
                 if n is not self.root and n.where == HOST and n.pins == 0 and not n.children]
 
-    def _remove_subtree(self, n: Node, gone: List[int]) -> None:
+    def _remove_subtree(self, n: Node, plan: Plan) -> None:
         for c in list(n.children.values()):
-            self._remove_subtree(c, gone)
+            self._remove_subtree(c, plan)
         assert n.pins == 0
         if n.where == GPU:
             self.free_dev.extend(n.dev_blocks)
         if n.host_valid:
+            # a copy to the host that this same request asked for a moment ago is void now
+            mine = set(n.host_slots)
+            kept = [(d, s) for d, s in plan.swap_out if s not in mine]
+            self.blocks_swapped_out -= len(plan.swap_out) - len(kept)
+            plan.swap_out[:] = kept
             self.free_host.extend(n.host_slots)
         del n.parent.children[n.doc]
-        gone.append(n.ident)
+        plan.evicted_host.append(n.ident)
 
     # ---- Algorithm 1, UPDATE_NODE_IN_GPU (both tiers' priorities are refreshed, see the header)
     def _update_node(self, node: Node, is_cached: bool, alpha: int, beta: int) -> None:
@@ -176,14 +182,14 @@ class KnowledgeTree:
         return ok, blocks
 
     # ---- host tier: make `required` slots free by dropping host-only leaves
-    def _evict_in_host(self, required: int, gone: List[int]) -> bool:
+    def _evict_in_host(self, required: int, plan: Plan) -> bool:
         while len(self.free_host) < required:
             S = self._host_leaves()
             if not S:
                 return False
             n = min(S, key=lambda x: (x.Priority[HOST], x.ident))
             self.Clock[HOST] = max(self.Clock[HOST], n.Priority[HOST])
-            self._remove_subtree(n, gone)
+            self._remove_subtree(n, plan)
         return True
 
     # ---- Algorithm 1, EVICT_IN_GPU, with the swap-out-only-once bookkeeping
@@ -200,13 +206,13 @@ class KnowledgeTree:
                 self.zero_copy_evictions += 1
             elif n.n_owned == 0:
                 n.host_valid = True  # nothing to copy
-            elif self._evict_in_host(n.n_owned, plan.evicted_host):
+            elif self._evict_in_host(n.n_owned, plan):
                 n.host_slots = [self.free_host.pop() for _ in range(n.n_owned)]
                 plan.swap_out.extend(zip(n.dev_blocks, n.host_slots))
                 self.blocks_swapped_out += n.n_owned
                 n.host_valid = True
             else:
-                self._remove_subtree(n, plan.evicted_host)  # frees its device blocks as well
+                self._remove_subtree(n, plan)  # frees its device blocks as well
                 continue
             self.free_dev.extend(n.dev_blocks)
             n.dev_blocks = []

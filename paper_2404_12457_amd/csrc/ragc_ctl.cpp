@@ -154,22 +154,37 @@ struct ragc_tree {
     }
 
     // a node leaves the cache together with everything below it
-    void remove_subtree(Node* n, std::vector<int64_t>& gone) {
+    void remove_subtree(Node* n, Request* rq) {
         // children in the order they were created (ids grow with creation)
         std::vector<Node*> kids;
         for (const auto& kv : n->children) kids.push_back(kv.second);
         std::sort(kids.begin(), kids.end(), [](const Node* a, const Node* b) { return a->id < b->id; });
-        for (Node* c : kids) remove_subtree(c, gone);
+        for (Node* c : kids) remove_subtree(c, rq);
         unlist(n);
         if (n->tier == kGpu) {
             free_dev.insert(free_dev.end(), n->dev.begin(), n->dev.end());
             --n_nodes_gpu;
             --n->parent->gpu_children;
         }
-        if (n->host_valid) free_host.insert(free_host.end(), n->host.begin(), n->host.end());
+        if (n->host_valid) {
+            // a copy to the host that this same request asked for a moment ago is void now
+            if (rq && !n->host.empty()) {
+                size_t kept = 0;
+                for (size_t i = 0; i < rq->out_slot.size(); ++i) {
+                    if (std::find(n->host.begin(), n->host.end(), rq->out_slot[i]) != n->host.end()) continue;
+                    rq->out_dev[kept] = rq->out_dev[i];
+                    rq->out_slot[kept] = rq->out_slot[i];
+                    ++kept;
+                }
+                swapped_out -= (int64_t)(rq->out_slot.size() - kept);
+                rq->out_dev.resize(kept);
+                rq->out_slot.resize(kept);
+            }
+            free_host.insert(free_host.end(), n->host.begin(), n->host.end());
+        }
         Node* p = n->parent;
         p->children.erase(n->doc);
-        gone.push_back(n->id);
+        if (rq) rq->evicted_host.push_back(n->id);
         by_id.erase(n->id);
         --n_nodes;
         delete n;
@@ -177,12 +192,12 @@ struct ragc_tree {
     }
 
     // host tier: free slots by dropping host-only leaves, lowest priority first
-    bool evict_in_host(size_t required, std::vector<int64_t>& gone) {
+    bool evict_in_host(size_t required, Request* rq) {
         while (free_host.size() < required) {
             if (candidates[kHost].empty()) return false;
             const auto top = *candidates[kHost].begin();
             clock[kHost] = std::max(clock[kHost], top.first);
-            remove_subtree(by_id.at(top.second), gone);
+            remove_subtree(by_id.at(top.second), rq);
         }
         return true;
     }
@@ -203,8 +218,8 @@ struct ragc_tree {
                 n->host_valid = true;
             } else {
                 // its own slot must not be taken from under it: the node is not a host candidate yet
-                if (!evict_in_host((size_t)owned, rq.evicted_host)) {
-                    remove_subtree(n, rq.evicted_host);
+                if (!evict_in_host((size_t)owned, &rq)) {
+                    remove_subtree(n, &rq);
                     continue;
                 }
                 for (int32_t i = 0; i < owned; ++i) {
@@ -249,10 +264,9 @@ struct ragc_tree {
     }
 
     ~ragc_tree() {
-        std::vector<int64_t> gone;
         for (auto& kv : requests)
             for (Node* n : kv.second.nodes) n->pins = 0;
-        while (!root.children.empty()) remove_subtree(root.children.begin()->second, gone);
+        while (!root.children.empty()) remove_subtree(root.children.begin()->second, nullptr);
     }
 };
 

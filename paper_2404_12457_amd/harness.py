@@ -130,3 +130,68 @@ class DeviceWorkload:
         w = self.w
         B.ragc_kv_swap(self.pool, self.host_k, self.host_v, w.kv_heads * 16 * w.head_dim, w.num_host_slots, dev_blocks,
                        host_slots, direction, flags, s)
+
+
+class LayeredCache:
+    """One paged K/V pool per transformer layer plus a pinned host pool per layer, all addressed by
+    the same block ids and host slots (the controller's plan applies to every layer), and the
+    stream choreography around the C-ABI calls: with `prefetch` the copies of layer l+1 run on a
+    side stream under the attention of layer l (the controller decides WHAT moves, the kernels
+    move it; this class only orders the calls).  Test and benchmark plumbing, no arithmetic."""
+
+    def __init__(self, layers: int, gpu_blocks: int, host_slots: int, kv_heads: int, head_dim: int, dtype: str = "bf16",
+                 device="cuda"):
+        self.layers, self.kv_heads, self.head_dim, self.dtype, self.device = layers, kv_heads, head_dim, dtype, device
+        td = torch_dtype(dtype)
+        shp = (gpu_blocks, kv_heads, 16, head_dim)
+        self.pool_k = [torch.full(shp, float("nan"), dtype=td, device=device) for _ in range(layers)]
+        self.pool_v = [torch.full(shp, float("nan"), dtype=td, device=device) for _ in range(layers)]
+        hshp = (max(host_slots, 1), kv_heads, 16, head_dim)
+        self.host_k = [torch.zeros(hshp, dtype=td).pin_memory() for _ in range(layers)]
+        self.host_v = [torch.zeros(hshp, dtype=td).pin_memory() for _ in range(layers)]
+        self.host_slots = max(host_slots, 1)
+        code = B.RAGC_DTYPE_BF16 if dtype == "bf16" else B.RAGC_DTYPE_F32
+        self.pools = [B.make_pool(self.pool_k[l], self.pool_v[l], gpu_blocks, kv_heads, head_dim, code) for l in range(layers)]
+        self.side = torch.cuda.Stream(device=device)
+        self.ready = [torch.cuda.Event() for _ in range(layers)]
+        self.begun = torch.cuda.Event()
+
+    def _swap(self, layer: int, dev, slots, direction: int, stream: int):
+        if len(dev):
+            B.ragc_kv_swap(self.pools[layer], self.host_k[layer], self.host_v[layer], self.kv_heads * 16 * self.head_dim,
+                           self.host_slots, dev, slots, direction, B.RAGC_SWAP_KERNEL, stream)
+
+    def execute(self, plan, q, k_new, v_new, q_heads: int, scale: float, prefetch: bool = True):
+        """Run one request through every layer: the plan's swap-outs, then its swap-ins, then
+        prefix-cached attention with the fused append.  q / k_new / v_new: one device tensor per
+        layer ([beta, H, D]).  Returns the per-layer outputs."""
+        main = torch.cuda.current_stream()
+        alpha, beta = int(plan.alpha), int(plan.beta)
+        hp, hn, hs = np.asarray([alpha], np.int32), np.asarray([beta], np.int32), np.asarray([0, beta], np.int32)
+        ht = np.ascontiguousarray(plan.block_table, np.int32).reshape(1, -1)
+        dev = [torch.from_numpy(a).to(self.device) for a in (hp, hn, hs, ht)]
+        batch = B.make_batch(1, ht.shape[1], dev[0], dev[1], dev[2], dev[3], hp, hn, hs, ht)
+        outs = [torch.empty_like(q[l]) for l in range(self.layers)]
+        copies = prefetch and (len(plan.swap_out_dev) or len(plan.swap_in_dev))
+        if copies:
+            # the copies may touch blocks that earlier work on the main stream still reads or writes
+            self.begun.record(main)
+            self.side.wait_event(self.begun)
+            for l in range(self.layers):
+                self._swap(l, plan.swap_out_dev, plan.swap_out_slot, B.RAGC_SWAP_TO_HOST, self.side.cuda_stream)
+                self._swap(l, plan.swap_in_dev, plan.swap_in_slot, B.RAGC_SWAP_TO_DEVICE, self.side.cuda_stream)
+                self.ready[l].record(self.side)
+        for l in range(self.layers):
+            if copies:
+                main.wait_event(self.ready[l])
+            elif not prefetch:
+                self._swap(l, plan.swap_out_dev, plan.swap_out_slot, B.RAGC_SWAP_TO_HOST, main.cuda_stream)
+                self._swap(l, plan.swap_in_dev, plan.swap_in_slot, B.RAGC_SWAP_TO_DEVICE, main.cuda_stream)
+            if beta > 0:
+                B.ragc_prefill_attn(self.pools[l], batch, q[l], k_new[l], v_new[l], outs[l], q_heads, scale,
+                                    B.RAGC_ATTN_APPEND_FUSED, None, 0, main.cuda_stream)
+        if copies:
+            # later work on the main stream may reuse what the side stream was given
+            self.side.wait_stream(main)
+        self._keep = (batch, dev, hp, hn, hs, ht)
+        return outs

@@ -217,6 +217,18 @@ def test_without_host_room_an_evicted_document_is_simply_freed():
     t.check_invariants()
 
 
+def test_a_copy_is_struck_from_the_list_when_its_node_leaves_the_cache_in_the_same_request():
+    t = _tree(4, 2)
+    t.end(t.begin([1], [32], 0).request_id)
+    t.end(t.begin([2], [32], 0).request_id)
+    b_blocks = list(t.find([2]).dev_blocks)
+    p = t.begin([3], [64], 0)  # D1 goes to the host (2 slots), then D2 needs them: D1 leaves the cache
+    assert p.evicted_gpu == [1, 2] and p.evicted_host == [1] and t.find([1]) is None
+    assert [d for d, _ in p.swap_out] == b_blocks and sorted(s for _, s in p.swap_out) == [0, 1]
+    assert t.blocks_swapped_out == 2
+    t.check_invariants()
+
+
 def test_random_trace_keeps_every_invariant():
     rng = random.Random(11)
     t = _tree(40, 60, lambda a, b: 5.0 + 0.01 * b + 1e-5 * a * b)
