@@ -116,6 +116,93 @@ def read_traffic(kernel_tag):
     return None
 
 
+def measure_cost_grid(harness, W, B, torch):
+    """T(alpha, beta) of the paper's cost model (Sec. 5.1, Algorithm 1), measured with this kernel:
+    one request with alpha cached and beta non-cached tokens, LLaMA2-7B head shape, one layer's
+    attention with the fused append.  Off-grid points are then measured as well and compared with
+    what ragc_cost_interp returns for them."""
+    from paper_2404_12457_amd import ctl
+
+    alphas, betas = [0, 512, 1024, 2048, 4096], [16, 64, 128, 256, 512, 1024]
+    probes = [(768, 96), (1536, 192), (3072, 384), (300, 700), (2500, 40)]
+
+    def one(a, b):
+        w = W.make_small("bf16", 32, 32, 128, [(a, b)], seed=1000 + a + b, sigma=0.5)
+        dw = harness.DeviceWorkload(w)
+        _, em = _time_steps(lambda i: dw.attn(B.RAGC_ATTN_APPEND_FUSED), 30, 5, torch)
+        del dw
+        return em * 1e3  # microseconds
+
+    t = [[one(a, b) for b in betas] for a in alphas]
+    grid = ctl.CostGrid(alphas, betas, t)
+    check = []
+    for a, b in probes:
+        m, e = one(a, b), ctl.ragc_cost_interp(grid, a, b)
+        check.append({"alpha": a, "beta": b, "measured_us": m, "interpolated_us": e, "rel_err": abs(e - m) / m})
+    torch.cuda.empty_cache()
+    return {"shape": "1 request, 32 heads MHA, head_dim 128, bf16, one layer, fused append", "alpha": alphas, "beta": betas,
+            "t_us": t, "off_grid": check, "max_rel_err": max(c["rel_err"] for c in check)}
+
+
+def measure_layer_prefetch(harness, B, torch):
+    """One request through 8 layers, each with its own pool: 4096 cached tokens that live in
+    pinned host memory (256 blocks per layer to bring in) and 512 new tokens, Mistral-7B head
+    shape.  Serial: copy then attention, layer after layer, on one stream.  Prefetch: the copies
+    of layer l+1 run on a side stream under the attention of layer l."""
+    from paper_2404_12457_amd import ctl
+
+    layers, hq, hkv, d, alpha, beta = 8, 32, 8, 128, 4096, 512
+    nblk = (alpha + beta) // 16
+    cache = harness.LayeredCache(layers, 1024, 512, hkv, d)
+    for l in range(layers):
+        cache.host_k[l].normal_(0, 0.5)
+        cache.host_v[l].normal_(0, 0.5)
+    i32 = lambda n: np.arange(n, dtype=np.int32)
+    e32, e64 = np.empty(0, np.int32), np.empty(0, np.int64)
+    plan = ctl.Plan(1, 1, alpha, beta, i32(nblk), e32, e32, i32(alpha // 16), i32(alpha // 16), e64, e64)
+    q = [torch.randn(beta, hq, d, device="cuda").mul_(0.5).to(torch.bfloat16) for _ in range(layers)]
+    kn = [torch.randn(beta, hkv, d, device="cuda").mul_(0.5).to(torch.bfloat16) for _ in range(layers)]
+    vn = [torch.randn(beta, hkv, d, device="cuda").mul_(0.5).to(torch.bfloat16) for _ in range(layers)]
+    scale = 1.0 / float(np.sqrt(d))
+    res = {}
+    for name, pf in (("serial_ms", False), ("prefetch_ms", True)):
+        _, em = _time_steps(lambda i: cache.execute(plan, q, kn, vn, hq, scale, prefetch=pf), 10, 2, torch)
+        cache.side.synchronize()
+        res[name] = em
+    noswap = ctl.Plan(1, 1, alpha, beta, i32(nblk), e32, e32, e32, e32, e64, e64)
+    _, em = _time_steps(lambda i: cache.execute(noswap, q, kn, vn, hq, scale, prefetch=False), 10, 2, torch)
+    res["attention_only_ms"] = em
+    res.update({"layers": layers, "blocks_swapped_in_per_layer": alpha // 16, "bytes_swapped_in": layers * (alpha // 16) * 2 * hkv * 16 * d * 2,
+                "shape": "1 request, 32/8 heads, head_dim 128, bf16, alpha 4096 (host-resident), beta 512"})
+    del cache
+    torch.cuda.empty_cache()
+    return res
+
+
+def measure_controller():
+    """The C++ knowledge tree on a Zipf(1.1) trace over 10,000 documents of 256-1024 tokens, top-2
+    retrieval, through the Python binding (begin + plan_read + end per request)."""
+    from paper_2404_12457_amd import ctl
+
+    rng = np.random.Generator(np.random.Philox(key=[7, 7]))
+    ndocs, nreq = 10000, 20000
+    lens = rng.integers(256, 1025, ndocs)
+    ranks = np.minimum(rng.zipf(1.1, (nreq, 2)) - 1, ndocs - 1)
+    grid = ctl.CostGrid([0.0, 8192.0], [1.0, 8192.0], [[10.0, 900.0], [30.0, 2500.0]])
+    tree = ctl.Tree(8192, 65536, grid)
+    t0 = time.perf_counter()
+    for i in range(nreq):
+        docs = [int(ranks[i, 0])] + ([int(ranks[i, 1])] if ranks[i, 1] != ranks[i, 0] else [])
+        p = tree.begin(docs, [int(lens[d]) for d in docs], 100)
+        tree.end(p.request_id)
+    dt = time.perf_counter() - t0
+    s = tree.stats()
+    return {"requests": nreq, "requests_per_s": nreq / dt, "hit_rate": s.docs_hit / s.docs_requested, "nodes": int(s.nodes),
+            "blocks_swapped_out": int(s.blocks_swapped_out), "blocks_swapped_in": int(s.blocks_swapped_in),
+            "zero_copy_evictions": int(s.zero_copy_evictions), "gpu_blocks": 8192, "host_slots": 65536}
+
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -251,6 +338,11 @@ def main():
                         "tflops_all_resident": w5.attn_flops() / em_alone / 1e9,
                         "mfma_frac_all_resident": w5.attn_flops() / em_alone / 1e9 / MFMA_BF16_PEAK_TFLOPS}
         del d5
+        torch.cuda.empty_cache()
+        # the controller side: measured cost model, layer-ahead copies over per-layer pools, tree throughput
+        extras["cost_grid"] = measure_cost_grid(harness, W, B, torch)
+        extras["layer_prefetch"] = measure_layer_prefetch(harness, B, torch)
+        extras["controller"] = measure_controller()
         result["other_workloads"] = extras
 
     if not args.no_cpu:

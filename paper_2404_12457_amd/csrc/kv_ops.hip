@@ -110,31 +110,36 @@ __global__ __launch_bounds__(256) void gather_kernel(PagedBatch b, int req, int 
     }
 }
 
-// grid.x = pair * 2 planes * segments; each workgroup moves kSwapSeg bytes of one
-// plane of one block, four 16-byte loads in flight per thread before the stores.
+// One unit = kSwapSeg bytes of one plane of one block (four 16-byte loads in flight per thread
+// before the stores); unit index = (pair * 2 + plane) * segs + seg.  The workgroups stride over
+// the units: the host link needs only a few dozen workgroups' worth of loads in flight, and a
+// small grid leaves the compute units to an attention kernel running next to the copies.
 constexpr int kSwapSeg = 256 * 16 * 4;
+constexpr int kSwapMaxWorkgroups = 32;  // measured: 16-64 reach the link's rate, 8 do not, hundreds block co-running kernels
 
 __global__ __launch_bounds__(256) void swap_kernel(char* __restrict__ dev_k, char* __restrict__ dev_v, long long dev_stride,
                                                    char* __restrict__ host_k, char* __restrict__ host_v, long long host_stride,
-                                                   long long plane_bytes, int segs, SwapPairs pairs, int to_device) {
-    const int seg = blockIdx.x % segs;
-    const int plane = (blockIdx.x / segs) & 1;
-    const int pair = blockIdx.x / (2 * segs);
-    char* d = (plane ? dev_v : dev_k) + (long long)pairs.dev[pair] * dev_stride;
-    char* h = (plane ? host_v : host_k) + (long long)pairs.slot[pair] * host_stride;
-    const char* src = to_device ? h : d;
-    char* dst = to_device ? d : h;
-    const long long base = (long long)seg * kSwapSeg + ((long long)threadIdx.x << 4);
-    u32x4 tmp[4];
+                                                   long long plane_bytes, int segs, int units, SwapPairs pairs, int to_device) {
+    for (int unit = blockIdx.x; unit < units; unit += gridDim.x) {
+        const int seg = unit % segs;
+        const int plane = (unit / segs) & 1;
+        const int pair = unit / (2 * segs);
+        char* d = (plane ? dev_v : dev_k) + (long long)pairs.dev[pair] * dev_stride;
+        char* h = (plane ? host_v : host_k) + (long long)pairs.slot[pair] * host_stride;
+        const char* src = to_device ? h : d;
+        char* dst = to_device ? d : h;
+        const long long base = (long long)seg * kSwapSeg + ((long long)threadIdx.x << 4);
+        u32x4 tmp[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const long long off = base + (long long)i * 4096;
-        if (off < plane_bytes) tmp[i] = *reinterpret_cast<const u32x4*>(src + off);
-    }
+        for (int i = 0; i < 4; ++i) {
+            const long long off = base + (long long)i * 4096;
+            if (off < plane_bytes) tmp[i] = *reinterpret_cast<const u32x4*>(src + off);
+        }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const long long off = base + (long long)i * 4096;
-        if (off < plane_bytes) *reinterpret_cast<u32x4*>(dst + off) = tmp[i];
+        for (int i = 0; i < 4; ++i) {
+            const long long off = base + (long long)i * 4096;
+            if (off < plane_bytes) *reinterpret_cast<u32x4*>(dst + off) = tmp[i];
+        }
     }
 }
 
@@ -175,8 +180,9 @@ hipError_t launch_swap(char* dev_k, char* dev_v, int64_t dev_block_bytes_stride,
                        int to_device, hipStream_t s) {
     if (n <= 0) return hipSuccess;
     const int segs = (int)((plane_block_bytes + kSwapSeg - 1) / kSwapSeg);
-    hipLaunchKernelGGL(swap_kernel, dim3(n * 2 * segs), dim3(256), 0, s, dev_k, dev_v, (long long)dev_block_bytes_stride,
-                       host_k, host_v, (long long)host_block_bytes_stride, (long long)plane_block_bytes, segs, pairs,
+    const int units = n * 2 * segs;
+    hipLaunchKernelGGL(swap_kernel, dim3(units < kSwapMaxWorkgroups ? units : kSwapMaxWorkgroups), dim3(256), 0, s, dev_k, dev_v, (long long)dev_block_bytes_stride,
+                       host_k, host_v, (long long)host_block_bytes_stride, (long long)plane_block_bytes, segs, units, pairs,
                        to_device);
     return hipGetLastError();
 }
