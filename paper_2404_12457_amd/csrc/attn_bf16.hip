@@ -22,6 +22,12 @@
 // overlaps the other's MFMAs.  With many work items NG = 1 and two workgroups share
 // a CU instead.
 //
+// A batch with few work items is also split along the keys ACROSS workgroups: a work item
+// then appears S times in the list, each copy walks 1/S of the key tiles and leaves its
+// unnormalised O and its (max, sum) per row in the caller's workspace, and attn_bf16_merge_kernel
+// combines the S partial results of every row.  This is what keeps a single request, or a
+// decode step, from running on a fraction of the chip.
+//
 // The products are computed transposed so that a lane owns ONE query row:
 //   S^T[key][row] = K . Q^T      A = K tile (LDS, 16-byte reads), B = Q (registers)
 //   O^T[d][row]  += V^T . P^T    A = V tile read with the transposing LDS load,
@@ -91,8 +97,13 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 
     const int last_row = min(row0 + TM, rows_total) - 1;
     const int kv_limit = P + div_g(last_row) + 1;  // keys [0, kv_limit) are visible to some row of the item
-    const int ntiles = (kv_limit + TN - 1) / TN;
-    const int nsteps = (ntiles + NG - 1) / NG;  // group `grp` takes tile step*NG + grp
+    const int ntiles_all = (kv_limit + TN - 1) / TN;
+    // key split across workgroups: copy `sidx` of S takes tiles [t_lo, ntiles)
+    const int S = (it.split >> 8) & 0xff, sidx = it.split & 0xff;
+    const int t_lo = ntiles_all * sidx / S;
+    const int ntiles = ntiles_all * (sidx + 1) / S;  // exclusive end of this copy's tiles
+    if (t_lo >= ntiles) return;                      // more copies than tiles: nothing for this one
+    const int nsteps = (ntiles - t_lo + NG - 1) / NG;  // group `grp` takes tile t_lo + step*NG + grp
 
     // ---- this lane's query row
     const int wrow0 = row0 + wq * 32;
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     int blk_base = 0;
     int blk_vec;
     {
-        const int e = (min(lane * NG + grp, ntiles - 1) * TN >> 4) + wq;
+        const int e = (min(t_lo + lane * NG + grp, ntiles - 1) * TN >> 4) + wq;
         blk_vec = e < nblk_item ? table[e] : 0;
     }
     bf16x8 qreg[KSTEPS];
@@ -163,11 +174,11 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     auto prepare = [&](int step) {
         if (step - blk_base >= 64) {
             blk_base = step;
-            const int e = (min((step + lane) * NG + grp, ntiles - 1) * TN >> 4) + wq;
+            const int e = (min(t_lo + (step + lane) * NG + grp, ntiles - 1) * TN >> 4) + wq;
             blk_vec = e < nblk_item ? table[e] : 0;
             asm volatile("" ::"v"(blk_vec));  // the compiler's wait for this load stays inside the branch
         }
-        const int tg = min(step * NG + grp, ntiles - 1);  // a group without a tile re-reads the last one (same count of loads)
+        const int tg = min(t_lo + step * NG + grp, ntiles - 1);  // a group without a tile re-reads the last one (same count of loads)
         const int kbase = tg * TN + wq * 16;
         const int blk = __builtin_amdgcn_readlane(blk_vec, step - blk_base);
         const uint32_t dst = smem_addr + (grp * RING + step % RING) * STAGEB + wq * 16 * ROWB;
@@ -253,7 +264,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         block_barrier();  // every wave's part is in LDS, and every wave is done with the previous step
         if (step + RING - 1 < nsteps) prepare(step + RING - 1);
 
-        const int tg = step * NG + grp;
+        const int tg = t_lo + step * NG + grp;
         const int base = tg * TN;
         if (!wave_active || tg >= ntiles || base >= wave_vis_max) {
             flush();
@@ -370,7 +381,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     // ---- fused append (after the key loop: nothing waits for it, and the fresh rows are L2-hot
     // because the loop has just read them as keys).  This work item owns the tokens whose first
     // row (head 0 of the group) it holds; 16-byte chunks, four per thread in flight.
-    if (a.fused_append) {
+    if (a.fused_append && sidx == S - 1) {  // the last copy always has tiles
         const int tok_lo = div_g(row0 + G - 1);
         const int tok_hi = min(N - 1, div_g(row0 + TM - 1));
         __bf16* wk = static_cast<__bf16*>(a.pool_k_w);
@@ -428,8 +439,11 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         if (wave_active) {
             const f32x4 ml = xw[DT * 4 * 64];
             const float m1 = ml[0], l1 = ml[1];
-            const float m = fmaxf(m_run, m1);  // group 0 always saw key 0: finite
-            const float s0f = __builtin_amdgcn_exp2f(m_run - m), s1f = __builtin_amdgcn_exp2f(m1 - m);
+            // a group (or, with a key split, both) may have seen no visible key of a row: weight 0
+            const float m = fmaxf(m_run, m1);
+            const float s0f = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m);
+            const float s1f = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+            m_run = m;
             l_run = l_run * s0f + l1 * s1f;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
@@ -453,6 +467,37 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     static_assert(32 * OROWB <= WSTRIDE * 4, "output patch fits the merge area");
     lds_char* const patch = lds0 + wq * (NG > 1 ? WSTRIDE * 4 : 32 * OROWB);
     const float l_tot = l_run + other_half(l_run);
+    if (S > 1) {
+        // ---- one of S copies of the item: leave O (unnormalised, fp32), max and sum of every row in the
+        // workspace; partial (item, copy, kv head) = [TM][D] floats of O, then [TM][2] floats (max, sum).
+        // Same turn through LDS as below, in two passes of D/2 floats per row.
+        float* const part = static_cast<float*>(a.partial) + ((long long)((it.split >> 16) * S + sidx) * Hkv + g) * (TM * (D + 2));
+        const int prow = wq * 32;
+        if (hf == 0) {
+            const float2 ml = {m_run, l_tot};
+            *reinterpret_cast<float2*>(part + TM * D + (prow + l32) * 2) = ml;
+        }
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int dtl = 0; dtl < DT / 2; ++dtl)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int dt = pass * (DT / 2) + dtl;
+                    const f32x4 v = {oacc[dt][i4 * 4], oacc[dt][i4 * 4 + 1], oacc[dt][i4 * 4 + 2], oacc[dt][i4 * 4 + 3]};
+                    *reinterpret_cast<__attribute__((address_space(3))) f32x4*>(patch + l32 * OROWB + (dtl * 32 + i4 * 8 + hf * 4) * 4) = v;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int p = 0; p < 32 / RPI; ++p) {
+                const int rr = p * RPI + lane / CPR;
+                const f32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(patch + rr * OROWB + (lane % CPR) * 16);
+                *reinterpret_cast<f32x4*>(part + (prow + rr) * D + pass * (D / 2) + (lane % CPR) * 4) = v;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the patch is rewritten by the next pass
+        }
+        return;
+    }
     const float inv = 1.f / l_tot;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -479,6 +524,63 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     }
 }
 
+// Combines the S partial results of every row of a split work item (see the end of
+// attn_bf16_kernel for the layout): out = sum_s O_s 2^(m_s - m) / sum_s l_s 2^(m_s - m), m = max_s m_s.
+// The list holds one entry per split item (its copy 0); one workgroup per (entry, kv head, run of
+// 256 / (D/4) rows): 4 consecutive d of one row per thread.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, AttnWorkList wl) {
+    constexpr int TPR = D / 4;          // threads per row
+    constexpr int RPW = 256 / TPR;      // rows per workgroup
+    constexpr int CHUNKS = TM / RPW;    // workgroups per (entry, kv head)
+    const int Hkv = a.b.kv_heads;
+    const int chunk = blockIdx.x % CHUNKS;
+    const int g = (blockIdx.x / CHUNKS) % Hkv;
+    const AttnItem it = wl.item[blockIdx.x / (CHUNKS * Hkv)];
+    const int S = (it.split >> 8) & 0xff;
+    const int G = a.group;
+    const uint32_t g_magic = a.group_magic;
+    auto div_g = [&](int x) { return g_magic ? (int)__umulhi((uint32_t)x, g_magic) : x; };
+    const int rows_total = it.new_len * G;
+    const int row0 = (it.req_tile & 0xffff) * TM;
+    const int rows_here = min(TM, rows_total - row0);
+    const int kv_limit = it.prefix_len + div_g(row0 + rows_here - 1) + 1;
+    const int ntiles_all = (kv_limit + TN - 1) / TN;
+    constexpr int PART = TM * (D + 2);
+    const float* const part0 = static_cast<const float*>(a.partial) + ((long long)(it.split >> 16) * S * Hkv + g) * PART;
+    const long long copy_stride = (long long)Hkv * PART;
+    const int d4 = threadIdx.x % TPR;
+    __bf16* const outp = static_cast<__bf16*>(a.out);
+    const int r = chunk * RPW + threadIdx.x / TPR;
+    if (r < rows_here) {
+        float m = -INFINITY;
+        for (int c = 0; c < S; ++c) {
+            if (ntiles_all * c / S >= ntiles_all * (c + 1) / S) continue;  // that copy had no tiles and wrote nothing
+            m = fmaxf(m, part0[c * copy_stride + TM * D + r * 2]);
+        }
+        float l = 0.f;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < S; ++c) {
+            if (ntiles_all * c / S >= ntiles_all * (c + 1) / S) continue;
+            const float* pc = part0 + c * copy_stride;
+            const float mc = pc[TM * D + r * 2], lc = pc[TM * D + r * 2 + 1];
+            const float wgt = mc == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc - m);  // a copy may hold no visible key of the row
+            const f32x4 o = *reinterpret_cast<const f32x4*>(pc + r * D + d4 * 4);
+            l += lc * wgt;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += o[e] * wgt;
+        }
+        const float inv = 1.f / l;
+        const int row = row0 + r;
+        const int tok = div_g(row);
+        const int head = g * G + (row - tok * G);
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[e] * inv);
+        *reinterpret_cast<bf16x4*>(outp + ((long long)(it.new_start + tok) * a.q_heads + head) * D + d4 * 4) = o4;
+    }
+}
+
 template <int D, int NG, int RING>
 void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
     hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
@@ -499,6 +601,15 @@ hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int var
         d64 ? launch_one<64, 2, 2>(a, wl, s) : launch_one<128, 2, 2>(a, wl, s);
     else
         d64 ? launch_one<64, 1, 2>(a, wl, s) : launch_one<128, 1, 2>(a, wl, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16_merge(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
+    if (wl.n <= 0) return hipSuccess;
+    if (a.b.head_dim == 64)
+        hipLaunchKernelGGL((attn_bf16_merge_kernel<64>), dim3(wl.n * a.b.kv_heads * (TM / 16)), dim3(256), 0, s, a, wl);
+    else
+        hipLaunchKernelGGL((attn_bf16_merge_kernel<128>), dim3(wl.n * a.b.kv_heads * (TM / 8)), dim3(256), 0, s, a, wl);
     return hipGetLastError();
 }
 

@@ -120,6 +120,55 @@ int hip_fail(hipError_t e, const char* what) {
     return fail(RAGC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// How the bf16 path will run a batch: the (request, 128-row tile) work items, most key tiles
+// first so the long ones start early; how many copies of each item share its keys; which
+// kernel shape; and the workspace the copies need.  ragc_prefill_attn_workspace and
+// ragc_prefill_attn both call this, so they always agree.
+struct Bf16Item {
+    int32_t cost;  // key tiles
+    ragc::AttnItem it;
+};
+struct Bf16Plan {
+    std::vector<Bf16Item> items;
+    int splits = 1;
+    int variant = ragc::kAttnVariantOneGroup;
+    int64_t workspace = 0;
+};
+
+int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, int group, uint32_t flags, Bf16Plan* plan) {
+    for (int r = 0; r < batch->num_reqs; ++r) {
+        const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
+        const int64_t rows = (int64_t)n * group;
+        const int64_t tiles = (rows + ragc::kAttnRowsPerItem - 1) / ragc::kAttnRowsPerItem;
+        if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
+        for (int t = 0; t < (int)tiles; ++t)
+            plan->items.push_back({ragc::attn_bf16_item_cost(p, n, group, t),
+                                   ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r], 1u << 8}});
+    }
+    std::stable_sort(plan->items.begin(), plan->items.end(), [](const Bf16Item& x, const Bf16Item& y) { return x.cost > y.cost; });
+    const int64_t wgs = (int64_t)plan->items.size() * pool->kv_heads;
+    const int64_t cus = cu_count();
+    // Fewer work items than CUs: split each along its keys until every CU has one, keeping at
+    // least eight key tiles per copy of the longest item (a copy costs about as much as ten tiles
+    // before its first and after its last one).  RAGC_ATTN_SPLITS overrides (tests).
+    int splits = 1;
+    if (!(flags & RAGC_ATTN_NO_SPLIT) && wgs > 0) {
+        splits = (int)std::min<int64_t>(cus / wgs, ragc::kAttnMaxSplits);
+        splits = std::min(splits, plan->items.front().cost / 8);
+        if (const char* force = std::getenv("RAGC_ATTN_SPLITS")) splits = std::min(std::atoi(force), ragc::kAttnMaxSplits);
+        if (splits < 1 || (int64_t)plan->items.size() * splits > 65535) splits = 1;
+    }
+    plan->splits = splits;
+    // With at least two workgroups per CU two 4-wave workgroups share a CU; otherwise one 8-wave
+    // workgroup divides its key tiles between two wave groups.  RAGC_ATTN_VARIANT overrides (tests).
+    plan->variant = wgs * splits >= 2 * cus ? ragc::kAttnVariantOneGroup : ragc::kAttnVariantTwoGroups;
+    if (const char* force = std::getenv("RAGC_ATTN_VARIANT")) plan->variant = std::atoi(force);
+    if (plan->variant < 0 || plan->variant >= ragc::kAttnVariantCount)
+        return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VARIANT %d unknown", plan->variant);
+    plan->workspace = splits > 1 ? (int64_t)plan->items.size() * splits * pool->kv_heads * ragc::attn_partial_bytes(pool->head_dim) : 0;
+    return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -135,20 +184,22 @@ int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_d
 }
 
 int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads, uint32_t flags) {
-    (void)flags;
     g_err[0] = 0;
-    if (!pool) return fail(RAGC_ERR_NULL, "pool is NULL");
-    if (!batch) return fail(RAGC_ERR_NULL, "batch is NULL");
-    if (q_heads <= 0 || pool->kv_heads <= 0 || q_heads % pool->kv_heads != 0)
+    if (int rc = check_pool(pool)) return rc;
+    if (flags & ~(RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT)) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
+    if (q_heads <= 0 || q_heads % pool->kv_heads != 0)
         return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
-    return 0;
+    BatchInfo info;
+    if (int rc = check_batch(pool, batch, false, &info)) return rc;
+    if (pool->dtype != RAGC_DTYPE_BF16 || batch->num_reqs == 0 || info.total_new == 0) return 0;
+    Bf16Plan plan;
+    if (int rc = plan_bf16(pool, batch, q_heads / pool->kv_heads, flags, &plan)) return rc;
+    return plan.workspace;
 }
 
 int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
                       void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     g_err[0] = 0;
     if (int rc = check_pool(pool)) return rc;
     if (flags & ~(RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT)) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
@@ -171,6 +222,7 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     a.out = out;
     a.pool_k_w = pool->k;
     a.pool_v_w = pool->v;
+    a.partial = nullptr;
     a.q_heads = q_heads;
     a.group = q_heads / pool->kv_heads;
     a.group_magic = a.group == 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + a.group - 1) / a.group);
@@ -184,33 +236,30 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
         if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
         return RAGC_OK;
     }
-    // bf16: work items (request, 128-row tile), most key tiles first so the long ones start early
-    struct Item {
-        int32_t cost;
-        ragc::AttnItem it;
-    };
-    std::vector<Item> items;
-    for (int r = 0; r < batch->num_reqs; ++r) {
-        const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
-        const int64_t rows = (int64_t)n * a.group;
-        const int64_t tiles = (rows + ragc::kAttnRowsPerItem - 1) / ragc::kAttnRowsPerItem;
-        if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
-        for (int t = 0; t < (int)tiles; ++t)
-            items.push_back({ragc::attn_bf16_item_cost(p, n, a.group, t),
-                             ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
+    Bf16Plan plan;
+    if (int rc = plan_bf16(pool, batch, a.group, flags, &plan)) return rc;
+    const int S = plan.splits;
+    if (plan.workspace > 0) {
+        if (!workspace || (int64_t)workspace_bytes < plan.workspace)
+            return fail(RAGC_ERR_WORKSPACE, "workspace of %lld bytes needed (ragc_prefill_attn_workspace), %zu given",
+                        (long long)plan.workspace, workspace_bytes);
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RAGC_ERR_ALIGN, "workspace must be 256-byte aligned");
+        a.partial = workspace;
     }
-    // With at least two work items per CU two 4-wave workgroups share a CU; otherwise one 8-wave
-    // workgroup splits the keys between two wave groups.  RAGC_ATTN_VARIANT overrides (tests).
-    int variant = (int64_t)items.size() * pool->kv_heads >= 2 * (int64_t)cu_count() ? ragc::kAttnVariantOneGroup
-                                                                                      : ragc::kAttnVariantTwoGroups;
-    if (const char* force = std::getenv("RAGC_ATTN_VARIANT")) variant = std::atoi(force);
-    if (variant < 0 || variant >= ragc::kAttnVariantCount) return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VARIANT %d unknown", variant);
-    std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.cost > y.cost; });
-    for (size_t i = 0; i < items.size(); i += ragc::kAttnMaxItems) {
-        ragc::AttnWorkList wl{};
-        wl.n = (int32_t)std::min<size_t>(ragc::kAttnMaxItems, items.size() - i);
-        for (int j = 0; j < wl.n; ++j) wl.item[j] = items[i + j].it;
-        const hipError_t e = ragc::launch_attn_bf16(a, wl, variant, s);
+    // every copy of an item is a list entry of its own; a launch takes kAttnMaxItems entries
+    const size_t per_launch = (size_t)ragc::kAttnMaxItems / S;
+    for (size_t i = 0; i < plan.items.size(); i += per_launch) {
+        ragc::AttnWorkList wl{}, leads{};
+        const size_t cnt = std::min(per_launch, plan.items.size() - i);
+        for (size_t j = 0; j < cnt; ++j)
+            for (int c = 0; c < S; ++c) {
+                ragc::AttnItem it = plan.items[i + j].it;
+                it.split = (uint32_t)c | (uint32_t)S << 8 | (uint32_t)(i + j) << 16;
+                wl.item[wl.n++] = it;
+                if (c == 0) leads.item[leads.n++] = it;
+            }
+        hipError_t e = ragc::launch_attn_bf16(a, wl, plan.variant, s);
+        if (e == hipSuccess && S > 1) e = ragc::launch_attn_bf16_merge(a, leads, s);
         if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
     }
     return RAGC_OK;

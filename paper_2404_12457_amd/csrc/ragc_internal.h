@@ -34,6 +34,7 @@ struct AttnLaunch {
     void* out;
     void* pool_k_w;  // writable aliases of the pool planes (fused append)
     void* pool_v_w;
+    void* partial;   // workspace for the partial results of work items split along the keys (bf16 path)
     int32_t q_heads;
     int32_t group;      // q_heads / kv_heads
     uint32_t group_magic;  // ceil(2^32 / group), 0 for group 1: row / group by one multiply in the kernels
@@ -49,7 +50,7 @@ hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 // them in the kernel argument buffer (no device staging); long lists go out in
 // several launches.
 constexpr int kAttnRowsPerItem = 128;
-constexpr int kAttnMaxItems = 224;
+constexpr int kAttnMaxItems = 160;
 // One work item carries the request's lengths, so a workgroup needs no memory round trip
 // before it can look up its first block ids.
 struct AttnItem {
@@ -57,7 +58,11 @@ struct AttnItem {
     int32_t prefix_len;
     int32_t new_len;
     int32_t new_start;
+    uint32_t split;      // copy index | copies << 8 | index of the item among the split items << 16
 };
+// bytes of one partial result: O [rows][D] fp32, then (max, sum) per row
+inline int64_t attn_partial_bytes(int head_dim) { return (int64_t)kAttnRowsPerItem * (head_dim + 2) * 4; }
+constexpr int kAttnMaxSplits = 16;
 struct AttnWorkList {
     int32_t n;
     int32_t pad[3];
@@ -71,6 +76,8 @@ enum AttnVariant {
 // number of 64-key tiles the work item (row tile `tile` of kAttnRowsPerItem rows) walks
 int attn_bf16_item_cost(int prefix, int new_len, int group, int tile);
 hipError_t launch_attn_bf16(const AttnLaunch& a, const AttnWorkList& wl, int variant, hipStream_t s);
+// second pass after a launch of split items: `wl` lists copy 0 of every item; combines the partial results into `out`
+hipError_t launch_attn_bf16_merge(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s);
 
 hipError_t launch_append(const PagedBatch& b, void* pool_k, void* pool_v, const void* k_new, const void* v_new,
                          int32_t total_new, int esize, hipStream_t s);

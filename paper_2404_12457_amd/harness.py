@@ -31,6 +31,16 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().cpu().numpy()
 
 
+def workspace_for(pool, batch, q_heads: int, flags: int = 0, device="cuda", have=None):
+    """(tensor or None, bytes) large enough for ragc_prefill_attn on this batch; `have` is reused if it suffices."""
+    need = B.ragc_prefill_attn_workspace(pool, batch, q_heads, flags)
+    if need == 0:
+        return have, (have.numel() if have is not None else 0)
+    if have is None or have.numel() < need:
+        have = torch.empty(need, dtype=torch.uint8, device=device)
+    return have, have.numel()
+
+
 class DeviceWorkload:
     """A Workload resident on the GPU: pool planes (poison everywhere except the
     cached blocks), Q / fresh K,V, tables, and the ragc structs pointing at them."""
@@ -103,14 +113,12 @@ class DeviceWorkload:
 
     def attn_batch(self, batch, flags: int = 0, stream: Optional[int] = None):
         s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        self.workspace, self.workspace_bytes = workspace_for(self.pool, batch, self.w.q_heads, flags, self.device, self.workspace)
         B.ragc_prefill_attn(self.pool, batch, self.q, self.k_new, self.v_new, self.out, self.w.q_heads,
                             self.w.softmax_scale, flags, self.workspace, self.workspace_bytes, s)
 
     def ensure_workspace(self, flags: int = 0):
-        need = B.ragc_prefill_attn_workspace(self.pool, self.batch, self.w.q_heads, flags)
-        if need > self.workspace_bytes:
-            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
-            self.workspace_bytes = need
+        self.workspace, self.workspace_bytes = workspace_for(self.pool, self.batch, self.w.q_heads, flags, self.device, self.workspace)
 
     def attn(self, flags: int = 0, stream: Optional[int] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         self.ensure_workspace(flags)
@@ -155,6 +163,7 @@ class LayeredCache:
         self.side = torch.cuda.Stream(device=device)
         self.ready = [torch.cuda.Event() for _ in range(layers)]
         self.begun = torch.cuda.Event()
+        self.workspace = None  # shared by the layers: their attention calls run one after the other on one stream
 
     def _swap(self, layer: int, dev, slots, direction: int, stream: int):
         if len(dev):
@@ -172,6 +181,7 @@ class LayeredCache:
         dev = [torch.from_numpy(a).to(self.device) for a in (hp, hn, hs, ht)]
         batch = B.make_batch(1, ht.shape[1], dev[0], dev[1], dev[2], dev[3], hp, hn, hs, ht)
         outs = [torch.empty_like(q[l]) for l in range(self.layers)]
+        self.workspace, ws_bytes = workspace_for(self.pools[0], batch, q_heads, B.RAGC_ATTN_APPEND_FUSED, self.device, self.workspace)
         copies = prefetch and (len(plan.swap_out_dev) or len(plan.swap_in_dev))
         if copies:
             # the copies may touch blocks that earlier work on the main stream still reads or writes
@@ -189,7 +199,7 @@ class LayeredCache:
                 self._swap(l, plan.swap_in_dev, plan.swap_in_slot, B.RAGC_SWAP_TO_DEVICE, main.cuda_stream)
             if beta > 0:
                 B.ragc_prefill_attn(self.pools[l], batch, q[l], k_new[l], v_new[l], outs[l], q_heads, scale,
-                                    B.RAGC_ATTN_APPEND_FUSED, None, 0, main.cuda_stream)
+                                    B.RAGC_ATTN_APPEND_FUSED, self.workspace, ws_bytes, main.cuda_stream)
         if copies:
             # later work on the main stream may reuse what the side stream was given
             self.side.wait_stream(main)

@@ -125,7 +125,8 @@ def test_output_is_invariant_under_block_placement(H, dtype):
 def test_requests_do_not_depend_on_batch_composition(H):
     w = W.make_small("bf16", 8, 2, 128, [(80, 30), (200, 150), (17, 64)], seed=31)
     dw = H.DeviceWorkload(w)
-    full = H.to_host(dw.attn()).copy()
+    # one kernel configuration for both runs: a key split would be chosen for the single requests only
+    full = H.to_host(dw.attn(B.RAGC_ATTN_NO_SPLIT)).copy()
     for r in range(w.num_reqs):
         s = w.new_slice(r)
         hp, hn = dw.h_prefix_len[r : r + 1].copy(), dw.h_new_len[r : r + 1].copy()
@@ -134,9 +135,13 @@ def test_requests_do_not_depend_on_batch_composition(H):
         batch = B.make_batch(1, w.table_stride, dw.d_prefix_len[r : r + 1], dw.d_new_len[r : r + 1], ns,
                              dw.d_block_table[r], hp, hn, hs, dw.h_block_table[r])
         out = torch.zeros_like(dw.q[s])
-        B.ragc_prefill_attn(dw.pool, batch, dw.q[s], dw.k_new[s], dw.v_new[s], out, w.q_heads, w.softmax_scale, 0,
-                            None, 0, torch.cuda.current_stream().cuda_stream)
+        B.ragc_prefill_attn(dw.pool, batch, dw.q[s], dw.k_new[s], dw.v_new[s], out, w.q_heads, w.softmax_scale,
+                            B.RAGC_ATTN_NO_SPLIT, None, 0, torch.cuda.current_stream().cuda_stream)
         assert np.array_equal(H.to_host(out), full[s])
+        ws, nb = H.workspace_for(dw.pool, batch, w.q_heads)  # and with whatever split the library picks: same to rounding
+        B.ragc_prefill_attn(dw.pool, batch, dw.q[s], dw.k_new[s], dw.v_new[s], out, w.q_heads, w.softmax_scale, 0, ws, nb,
+                            torch.cuda.current_stream().cuda_stream)
+        assert np.max(np.abs(W.to_f64(H.to_host(out), "bf16") - W.to_f64(full[s], "bf16"))) <= 4e-3
 
 
 def test_requests_sharing_a_block_chain_and_query_agree(H):
@@ -210,7 +215,8 @@ def test_followup_request_reads_appended_blocks(H):
     batch = B.make_batch(1, w.table_stride, dp, dn, ds, dw.d_block_table, hp, hn, hs, dw.h_block_table)
     dq, dk, dv = (H.to_device(x, "bf16") for x in (q2, k2, v2))
     out = torch.zeros_like(dq)
-    B.ragc_prefill_attn(dw.pool, batch, dq, dk, dv, out, 8, w.softmax_scale, 0, None, 0,
+    ws, nb = H.workspace_for(dw.pool, batch, 8)
+    B.ragc_prefill_attn(dw.pool, batch, dq, dk, dv, out, 8, w.softmax_scale, 0, ws, nb,
                         torch.cuda.current_stream().cuda_stream)
     kf, vf = w.full_kv(0)
     kall = np.concatenate([kf, k2]), np.concatenate([vf, v2])
@@ -234,8 +240,9 @@ def test_chunked_prefill_equals_single_call(H):
         hs = np.array([0, hi - lo], np.int32)
         ds = torch.tensor(hs, device="cuda")
         batch = B.make_batch(1, w.table_stride, dp, dn, ds, two.d_block_table, hp, hn, hs, two.h_block_table)
+        ws, nb = H.workspace_for(two.pool, batch, 8, B.RAGC_ATTN_APPEND_FUSED)
         B.ragc_prefill_attn(two.pool, batch, two.q[lo:hi], two.k_new[lo:hi], two.v_new[lo:hi], out[lo:hi], 8,
-                            w.softmax_scale, B.RAGC_ATTN_APPEND_FUSED, None, 0, st)
+                            w.softmax_scale, B.RAGC_ATTN_APPEND_FUSED, ws, nb, st)
         torch.cuda.synchronize()
     got = W.to_f64(H.to_host(out), "bf16")
     want = U.oracle_all(w)
@@ -318,6 +325,48 @@ def test_every_kernel_variant_matches_oracle(H, variant, monkeypatch):
     assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
     assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
     _check_all(H, W.make_small("bf16", 4, 4, 64, [(700, 100), (5, 260)], seed=7002, q_gain=6.0))
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("splits", [2, 3, 7, 16])
+def test_key_split_across_workgroups_matches_oracle(H, variant, splits, monkeypatch):
+    """With few work items the library splits each one along its keys over several workgroups and
+    merges their partial results; force the number of copies (RAGC_ATTN_SPLITS) on batches whose
+    items have more, as many and fewer key tiles than copies, rows that see no key of a copy,
+    decode steps (one new token), and check the fused append (done by the last copy)."""
+    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
+    monkeypatch.setenv("RAGC_ATTN_SPLITS", str(splits))
+    w = W.make_small("bf16", 8, 2, 128, [(0, 17), (37, 20), (64, 1), (100, 133), (15, 0), (300, 250), (1030, 70), (2000, 1)], seed=7101)
+    dw = H.DeviceWorkload(w)
+    assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, B.RAGC_ATTN_APPEND_FUSED) > 0
+    assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, B.RAGC_ATTN_NO_SPLIT) == 0
+    with pytest.raises(B.RagcError) as e:  # no workspace given
+        B.ragc_prefill_attn(dw.pool, dw.batch, dw.q, dw.k_new, dw.v_new, dw.out, w.q_heads, w.softmax_scale, 0, None, 0, 0)
+    assert e.value.code == B.RAGC_ERR_WORKSPACE
+    dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    pk, pv = w.pool_image()
+    OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
+    assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
+    assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
+    _check_all(H, W.make_small("bf16", 4, 4, 64, [(700, 100), (5, 260), (900, 1)], seed=7102, q_gain=6.0))
+    # the same result with and without the split, bit for bit in what is unique: the appended pool
+    _, got_split, want = _check_all(H, W.make_small("bf16", 32, 8, 128, [(4096, 1)] * 3, seed=7103))
+    monkeypatch.setenv("RAGC_ATTN_SPLITS", "1")
+    _, got_one, _ = _check_all(H, W.make_small("bf16", 32, 8, 128, [(4096, 1)] * 3, seed=7103))
+    assert np.max(np.abs(got_split - got_one)) <= 2e-3
+
+
+def test_split_is_chosen_for_a_single_request_and_for_decode_steps(H):
+    """No override: one request with a long cached prefix, and a small decode batch, are split
+    (the workspace query says so) and match the oracle; a batch that fills the chip is not."""
+    for lens, hq, hkv in (([(4096, 48)], 32, 32), ([(3000, 1)] * 4, 64, 8), ([(1500, 300)], 32, 8)):
+        w = W.make_small("bf16", hq, hkv, 128, lens, seed=7200 + hq)
+        dw = H.DeviceWorkload(w)
+        assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, 0) > 0, lens
+        _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    w = W.make_config(2)
+    dw = H.DeviceWorkload(w)
+    assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, 0) == 0
 
 
 def test_many_work_items_take_several_launches(H):
