@@ -284,6 +284,17 @@ class KnowledgeTree:
         self.next_request += 1
         return plan
 
+    def peek(self, doc_ids: Sequence[int], doc_lens: Sequence[int], question_len: int) -> Tuple[int, int]:
+        """(cached length alpha, computation length beta) the request would get now; nothing changes."""
+        cur, matched_end = self.root, 0
+        for d in doc_ids:
+            cur = cur.children.get(d)
+            if cur is None:
+                break
+            matched_end = cur.tok_end
+        alpha = matched_end // BLOCK * BLOCK
+        return alpha, sum(doc_lens) + question_len - alpha
+
     def end(self, request_id: int) -> None:
         nodes, private = self.requests.pop(request_id)
         for n in nodes:
@@ -327,3 +338,37 @@ class KnowledgeTree:
             used_dev += private
         assert len(set(used_dev)) == len(used_dev) and not set(used_dev) & set(self.free_dev)
         assert len(set(used_host)) == len(used_host) and not set(used_host) & set(self.free_host)
+
+
+# ----------------------------------------------------------------------------- cache-aware reordering
+class ReorderQueue:
+    """Waiting requests, served by OrderPriority = cached length / computation length against the
+    tree as it is at the moment of the choice (paper Sec. 5.2); equal priorities go to the request
+    that arrived first.  Starvation window: a request that has seen `window` later arrivals served
+    before it is served next, oldest first.  (The paper gives the priority and the existence of a
+    window; how the window counts is this reading.)"""
+
+    def __init__(self, window: int):
+        self.window = window
+        self.waiting: List[list] = []  # [tag, doc_ids, doc_lens, question_len, times passed over]
+
+    def push(self, tag: int, doc_ids: Sequence[int], doc_lens: Sequence[int], question_len: int) -> None:
+        self.waiting.append([tag, list(doc_ids), list(doc_lens), question_len, 0])
+
+    def pop(self, tree: KnowledgeTree):
+        """The next request to serve: (tag, doc_ids, doc_lens, question_len)."""
+        assert self.waiting
+        starved = [i for i, w in enumerate(self.waiting) if w[4] >= self.window]
+        if starved:
+            pick = starved[0]
+        else:
+            best = None
+            for i, w in enumerate(self.waiting):
+                alpha, beta = tree.peek(w[1], w[2], w[3])
+                prio = alpha / beta if beta > 0 else float("inf")
+                if best is None or prio > best:
+                    best, pick = prio, i
+        for w in self.waiting[:pick]:
+            w[4] += 1  # served before a request that arrived earlier
+        tag, ids, lens, q, _ = self.waiting.pop(pick)
+        return tag, ids, lens, q

@@ -250,3 +250,51 @@ def test_random_trace_keeps_every_invariant():
         live.append(p.request_id)
         t.check_invariants()
     assert t.zero_copy_evictions > 0 and t.blocks_swapped_in > 0 and 0.0 < t.hit_rate() < 1.0
+
+
+# ---------------------------------------------------------------- cache-aware reordering (Sec. 5.2)
+def _serve(t, q):
+    order, hits = [], 0
+    while q.waiting:
+        tag, ids, lens, ql = q.pop(t)
+        p = t.begin(ids, lens, ql)
+        hits += p.matched_docs
+        t.end(p.request_id)
+        order.append(tag)
+    return order, hits
+
+
+def test_reordering_example_of_the_paper():
+    """Requests alternate between D1 and D2, the cache holds one document: in arrival order nothing
+    hits; by OrderPriority the order is Q1 Q3 Q5 Q2 Q4 Q6 and 4 of 6 hit (the paper's 66 %)."""
+    def six(window):
+        t = _tree(4, 0)  # one 64-token document
+        q = KT.ReorderQueue(window)
+        for i in range(1, 7):
+            q.push(i, [1 if i % 2 else 2], [64], 0)
+        return _serve(t, q)
+
+    assert six(window=100) == ([1, 3, 5, 2, 4, 6], 4)
+    assert six(window=0) == ([1, 2, 3, 4, 5, 6], 0)  # no reordering allowed: arrival order, zero hits
+
+
+def test_larger_cached_part_and_shorter_computation_go_first():
+    t = _tree(64, 64)
+    t.end(t.begin([1], [32], 0).request_id)
+    t.end(t.begin([2], [64], 0).request_id)
+    q = KT.ReorderQueue(100)
+    q.push(10, [1], [32], 32)   # cached 32, compute 32 -> 1
+    q.push(11, [2], [64], 32)   # cached 64, compute 32 -> 2: same computation, more cached
+    q.push(12, [2], [64], 16)   # cached 64, compute 16 -> 4: same cached, less computation
+    q.push(13, [3], [64], 16)   # nothing cached -> 0
+    assert [q.pop(t)[0] for _ in range(4)] == [12, 11, 10, 13]
+
+
+def test_starvation_window_bounds_how_often_a_request_is_passed_over():
+    t = _tree(64, 64)
+    t.end(t.begin([1], [64], 0).request_id)
+    q = KT.ReorderQueue(2)
+    q.push(1, [9], [64], 8)  # never cached: always the lowest priority
+    for i in range(2, 7):
+        q.push(i, [1], [64], 8)
+    assert [q.pop(t)[0] for _ in range(6)] == [2, 3, 1, 4, 5, 6]  # passed over twice, then served
