@@ -1,6 +1,6 @@
 /* ragc_ctl.h — host-side controller of the paged K/V cache: knowledge tree, prefix matching,
  * PGDSF replacement over a GPU tier and a host tier, swap-out-only-once bookkeeping and the
- * cost model T(alpha, beta).  Plain C ABI, CPU only, no GPU call is made here: the functions
+ * cost model T(alpha, beta), and the cache-aware request queue.  Plain C ABI, CPU only, no GPU call is made here: the functions
  * turn a request's document sequence into the inputs of ragc_prefill_attn / ragc_kv_swap
  * (block table row, cached length, swap lists).  Everything is host memory; arrays passed in
  * are read during the call only, arrays passed out are caller-owned with stated capacities.
@@ -123,6 +123,26 @@ int ragc_tree_find(const ragc_tree* tree, const int64_t* doc_path, int32_t n, ra
 
 /* Frequencies count retrievals within a time window (Sec. 5.1): start a new window. */
 int ragc_tree_reset_frequencies(ragc_tree* tree);
+
+/* Cached length alpha and computation length beta the request would get from ragc_tree_begin now;
+ * nothing changes. */
+int ragc_tree_peek(const ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
+                   int32_t question_len, int32_t* alpha, int32_t* beta);
+
+/* Cache-aware reordering (paper Sec. 5.2): waiting requests are served by
+ * OrderPriority = cached length / computation length, evaluated against the tree at the moment of
+ * the choice; equal priorities go to the request that arrived first.  Starvation window (the paper
+ * says there is one, not how it counts): a request that has seen `window` later arrivals served
+ * before it is served next, oldest first; window 0 is arrival order. */
+typedef struct ragc_queue ragc_queue; /* opaque */
+ragc_queue* ragc_queue_create(int32_t window);
+void ragc_queue_destroy(ragc_queue* queue);
+/* The arrays are copied; `tag` is the caller's name for the request. */
+int ragc_queue_push(ragc_queue* queue, int64_t tag, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
+                    int32_t question_len);
+/* Removes the request to serve next and writes its tag; RAGC_ERR_RANGE if nothing waits. */
+int ragc_queue_pop(ragc_queue* queue, const ragc_tree* tree, int64_t* tag);
+int32_t ragc_queue_size(const ragc_queue* queue);
 
 #ifdef __cplusplus
 }

@@ -472,10 +472,110 @@ int ragc_tree_find(const ragc_tree* tree, const int64_t* doc_path, int32_t n, ra
     return 0;
 }
 
+// cached and computation length of a request against the tree as it is (no state change)
+static void peek_lengths(const ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
+                         int32_t question_len, int64_t* alpha, int64_t* beta) {
+    const Node* cur = &tree->root;
+    int64_t matched_end = 0, total = question_len;
+    for (int32_t i = 0; i < n_docs; ++i) total += doc_lens[i];
+    for (int32_t i = 0; i < n_docs; ++i) {
+        const auto it = cur->children.find(doc_ids[i]);
+        if (it == cur->children.end()) break;
+        cur = it->second;
+        matched_end = cur->tok_end();
+    }
+    *alpha = matched_end / kBlk * kBlk;
+    *beta = total - *alpha;
+}
+
+int ragc_tree_peek(const ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
+                   int32_t question_len, int32_t* alpha, int32_t* beta) {
+    if (!tree || !alpha || !beta || (n_docs > 0 && (!doc_ids || !doc_lens))) return set_error(RAGC_ERR_NULL, "a required pointer is NULL");
+    if (n_docs < 0 || question_len < 0) return set_error(RAGC_ERR_RANGE, "n_docs %d / question_len %d must not be negative", n_docs, question_len);
+    int64_t a = 0, b = 0;
+    peek_lengths(tree, doc_ids, doc_lens, n_docs, question_len, &a, &b);
+    *alpha = (int32_t)a;
+    *beta = (int32_t)b;
+    return 0;
+}
+
 int ragc_tree_reset_frequencies(ragc_tree* tree) {
     if (!tree) return set_error(RAGC_ERR_NULL, "tree is NULL");
     for (auto& kv : tree->by_id) kv.second->frequency = 0;
     return 0;
 }
+
+// ---- cache-aware reordering (paper Sec. 5.2)
+struct ragc_queue {
+    struct Waiting {
+        int64_t tag;
+        std::vector<int64_t> ids;
+        std::vector<int32_t> lens;
+        int32_t question_len;
+        int32_t passed_over;
+    };
+    int32_t window = 0;
+    std::deque<Waiting> waiting;  // in arrival order
+};
+
+ragc_queue* ragc_queue_create(int32_t window) {
+    if (window < 0) {
+        set_error(RAGC_ERR_RANGE, "window %d must not be negative", window);
+        return nullptr;
+    }
+    ragc_queue* q = new ragc_queue();
+    q->window = window;
+    return q;
+}
+
+void ragc_queue_destroy(ragc_queue* queue) { delete queue; }
+
+int ragc_queue_push(ragc_queue* queue, int64_t tag, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
+                    int32_t question_len) {
+    if (!queue || (n_docs > 0 && (!doc_ids || !doc_lens))) return set_error(RAGC_ERR_NULL, "a required pointer is NULL");
+    if (n_docs < 0 || question_len < 0) return set_error(RAGC_ERR_RANGE, "n_docs %d / question_len %d must not be negative", n_docs, question_len);
+    ragc_queue::Waiting w;
+    w.tag = tag;
+    w.ids.assign(doc_ids, doc_ids + n_docs);
+    w.lens.assign(doc_lens, doc_lens + n_docs);
+    w.question_len = question_len;
+    w.passed_over = 0;
+    queue->waiting.push_back(std::move(w));
+    return 0;
+}
+
+int ragc_queue_pop(ragc_queue* queue, const ragc_tree* tree, int64_t* tag) {
+    if (!queue || !tree || !tag) return set_error(RAGC_ERR_NULL, "queue, tree or tag is NULL");
+    if (queue->waiting.empty()) return set_error(RAGC_ERR_RANGE, "no request is waiting");
+    size_t pick = queue->waiting.size();
+    for (size_t i = 0; i < queue->waiting.size(); ++i)
+        if (queue->waiting[i].passed_over >= queue->window) {
+            pick = i;  // the oldest request whose window is used up
+            break;
+        }
+    if (pick == queue->waiting.size()) {
+        // OrderPriority = cached / computation length, compared as a fraction; ties keep the earlier arrival
+        int64_t best_a = 0, best_b = 1;
+        bool have = false;
+        for (size_t i = 0; i < queue->waiting.size(); ++i) {
+            const auto& w = queue->waiting[i];
+            int64_t a = 0, b = 0;
+            peek_lengths(tree, w.ids.data(), w.lens.data(), (int32_t)w.ids.size(), w.question_len, &a, &b);
+            const bool better = !have || (b == 0 ? (best_b != 0) : (best_b != 0 && a * best_b > best_a * b));
+            if (better) {
+                have = true;
+                best_a = a;
+                best_b = b;
+                pick = i;
+            }
+        }
+    }
+    for (size_t i = 0; i < pick; ++i) queue->waiting[i].passed_over += 1;
+    *tag = queue->waiting[pick].tag;
+    queue->waiting.erase(queue->waiting.begin() + (long)pick);
+    return 0;
+}
+
+int32_t ragc_queue_size(const ragc_queue* queue) { return queue ? (int32_t)queue->waiting.size() : 0; }
 
 }  // extern "C"

@@ -13,7 +13,8 @@ import numpy as np
 from . import binding as B
 
 EXPORTS = ["ragc_cost_interp", "ragc_tree_create", "ragc_tree_destroy", "ragc_tree_begin", "ragc_tree_plan_read",
-           "ragc_tree_end", "ragc_tree_get_stats", "ragc_tree_find", "ragc_tree_reset_frequencies"]
+           "ragc_tree_end", "ragc_tree_get_stats", "ragc_tree_find", "ragc_tree_reset_frequencies", "ragc_tree_peek",
+           "ragc_queue_create", "ragc_queue_destroy", "ragc_queue_push", "ragc_queue_pop", "ragc_queue_size"]
 
 _D, _I32, _I64, _P = ctypes.c_double, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
 
@@ -70,6 +71,18 @@ def _lib():
         lib.ragc_tree_find.argtypes = [_P, _P, _I32, _P]
         lib.ragc_tree_reset_frequencies.restype = ctypes.c_int
         lib.ragc_tree_reset_frequencies.argtypes = [_P]
+        lib.ragc_tree_peek.restype = ctypes.c_int
+        lib.ragc_tree_peek.argtypes = [_P, _P, _P, _I32, _I32, _P, _P]
+        lib.ragc_queue_create.restype = _P
+        lib.ragc_queue_create.argtypes = [_I32]
+        lib.ragc_queue_destroy.restype = None
+        lib.ragc_queue_destroy.argtypes = [_P]
+        lib.ragc_queue_push.restype = ctypes.c_int
+        lib.ragc_queue_push.argtypes = [_P, _I64, _P, _P, _I32, _I32]
+        lib.ragc_queue_pop.restype = ctypes.c_int
+        lib.ragc_queue_pop.argtypes = [_P, _P, _P]
+        lib.ragc_queue_size.restype = _I32
+        lib.ragc_queue_size.argtypes = [_P]
         _ready = True
     return lib
 
@@ -162,3 +175,40 @@ class Tree:
 
     def reset_frequencies(self) -> None:
         _check(_lib().ragc_tree_reset_frequencies(self._h))
+
+    def peek(self, doc_ids: Sequence[int], doc_lens: Sequence[int], question_len: int):
+        ids = np.ascontiguousarray(doc_ids, np.int64)
+        lens = np.ascontiguousarray(doc_lens, np.int32)
+        a, b = _I32(), _I32()
+        _check(_lib().ragc_tree_peek(self._h, ids.ctypes.data, lens.ctypes.data, ids.size, question_len, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+
+class Queue:
+    """ragc_queue_*: cache-aware reordering of waiting requests."""
+
+    def __init__(self, window: int):
+        self._h = _lib().ragc_queue_create(window)
+        if not self._h:
+            raise B.RagcError(-3, B.load().ragc_last_error().decode())
+
+    def close(self) -> None:
+        if self._h:
+            _lib().ragc_queue_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def push(self, tag: int, doc_ids: Sequence[int], doc_lens: Sequence[int], question_len: int) -> None:
+        ids = np.ascontiguousarray(doc_ids, np.int64)
+        lens = np.ascontiguousarray(doc_lens, np.int32)
+        _check(_lib().ragc_queue_push(self._h, tag, ids.ctypes.data, lens.ctypes.data, ids.size, question_len))
+
+    def pop(self, tree: Tree) -> int:
+        tag = _I64()
+        _check(_lib().ragc_queue_pop(self._h, tree._h, ctypes.byref(tag)))
+        return tag.value
+
+    def __len__(self) -> int:
+        return int(_lib().ragc_queue_size(self._h))

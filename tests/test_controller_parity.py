@@ -140,3 +140,60 @@ def test_controller_rejects_bad_arguments_without_changing_anything():
     assert (s.nodes, s.free_gpu_blocks, s.docs_requested) == (1, 6, 1)
     with pytest.raises(B.RagcError):
         C.Tree(8, 8, C.CostGrid([0.0, 0.0], BETAS, np.zeros((2, len(BETAS)))))  # alpha not increasing
+
+
+@pytest.mark.parametrize("window,seed", [(0, 1), (3, 2), (1000, 3)])
+def test_reordering_queue_serves_in_the_same_order(window, seed):
+    """Cache-aware reordering (Sec. 5.2): requests arrive in bursts, are served one at a time by
+    OrderPriority against the current tree; the C++ queue and the oracle pick the same request
+    every time and report the same cached / computation lengths."""
+    rng = random.Random(seed)
+    to, tc = _pair(64, 128, lambda a, b: 2.0 + 0.05 * b + 1e-5 * a * b)
+    qo, qc = KT.ReorderQueue(window), C.Queue(window)
+    lens = {d: rng.randrange(8, 120) for d in range(25)}
+    reqs, tag, served = {}, 0, []
+    for burst in range(120):
+        for _ in range(rng.randrange(1, 6)):
+            docs = list(dict.fromkeys(min(int(rng.paretovariate(1.0)) - 1, 24) for _ in range(rng.randrange(1, 4))))
+            reqs[tag] = (docs, [lens[d] for d in docs], rng.randrange(0, 40))
+            qo.push(tag, *reqs[tag])
+            qc.push(tag, *reqs[tag])
+            assert tc.peek(*reqs[tag]) == to.peek(*reqs[tag])
+            tag += 1
+        for _ in range(rng.randrange(1, 5)):
+            if not qo.waiting:
+                break
+            want = qo.pop(to)[0]
+            assert qc.pop(tc) == want
+            served.append(want)
+            docs, dl, q = reqs[want]
+            if sum(dl) + q == 0:
+                continue
+            po, pc = to.begin(docs, dl, q), tc.begin(docs, dl, q)
+            _same_plan(po, pc)
+            to.end(po.request_id)
+            tc.end(pc.request_id)
+    assert len(qc) == len(qo.waiting)
+    if window == 0:
+        assert served == sorted(served)
+    else:
+        assert served != sorted(served)
+    with pytest.raises(B.RagcError):
+        C.Queue(0).pop(tc)
+
+
+def test_reordering_example_of_the_paper_through_the_library():
+    """Requests alternate between D1 and D2, the cache holds one document: served by OrderPriority
+    the order is Q1 Q3 Q5 Q2 Q4 Q6 and 4 of 6 hit (Sec. 5.2)."""
+    tc = C.Tree(4, 0, C.CostGrid(ALPHAS, BETAS, _grid(lambda a, b: b)))
+    q = C.Queue(100)
+    for i in range(1, 7):
+        q.push(i, [1 if i % 2 else 2], [64], 0)
+    order = []
+    while len(q):
+        i = q.pop(tc)
+        p = tc.begin([1 if i % 2 else 2], [64], 0)
+        tc.end(p.request_id)
+        order.append(i)
+    s = tc.stats()
+    assert order == [1, 3, 5, 2, 4, 6] and (s.docs_hit, s.docs_requested) == (4, 6)
