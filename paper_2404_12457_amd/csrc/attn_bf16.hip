@@ -43,7 +43,9 @@ namespace {
 
 constexpr int TM = kAttnRowsPerItem;  // rows per work item
 
-template <int D, int NG, int RING>
+// SPLIT: the list holds several copies of every item, each with a share of the key tiles (a
+// separate instantiation, so that the common unsplit kernel carries none of it).
+template <int D, int NG, int RING, bool SPLIT>
 __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn_bf16_kernel(AttnLaunch a, AttnWorkList wl) {
     constexpr int CPR = D / 8;          // 16-byte chunks per K/V row
     constexpr int ROWB = D * 2;         // bytes per row
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int kv_limit = P + div_g(last_row) + 1;  // keys [0, kv_limit) are visible to some row of the item
     const int ntiles_all = (kv_limit + TN - 1) / TN;
     // key split across workgroups: copy `sidx` of S takes tiles [t_lo, ntiles)
-    const int S = (it.split >> 8) & 0xff, sidx = it.split & 0xff;
+    const int S = SPLIT ? wl.splits : 1, sidx = SPLIT ? item % S : 0;
     const int t_lo = ntiles_all * sidx / S;
     const int ntiles = ntiles_all * (sidx + 1) / S;  // exclusive end of this copy's tiles
     if (t_lo >= ntiles) return;                      // more copies than tiles: nothing for this one
@@ -467,11 +469,11 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     static_assert(32 * OROWB <= WSTRIDE * 4, "output patch fits the merge area");
     lds_char* const patch = lds0 + wq * (NG > 1 ? WSTRIDE * 4 : 32 * OROWB);
     const float l_tot = l_run + other_half(l_run);
-    if (S > 1) {
+    if (SPLIT) {
         // ---- one of S copies of the item: leave O (unnormalised, fp32), max and sum of every row in the
         // workspace; partial (item, copy, kv head) = [TM][D] floats of O, then [TM][2] floats (max, sum).
         // Same turn through LDS as below, in two passes of D/2 floats per row.
-        float* const part = static_cast<float*>(a.partial) + ((long long)((it.split >> 16) * S + sidx) * Hkv + g) * (TM * (D + 2));
+        float* const part = static_cast<float*>(a.partial) + ((long long)(wl.part_base + item) * Hkv + g) * (TM * (D + 2));
         const int prow = wq * 32;
         if (hf == 0) {
             const float2 ml = {m_run, l_tot};
@@ -536,8 +538,9 @@ __global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, Attn
     const int Hkv = a.b.kv_heads;
     const int chunk = blockIdx.x % CHUNKS;
     const int g = (blockIdx.x / CHUNKS) % Hkv;
-    const AttnItem it = wl.item[blockIdx.x / (CHUNKS * Hkv)];
-    const int S = (it.split >> 8) & 0xff;
+    const int lead = blockIdx.x / (CHUNKS * Hkv);  // the list holds copy 0 of every split item, in launch order
+    const AttnItem it = wl.item[lead];
+    const int S = wl.splits;
     const int G = a.group;
     const uint32_t g_magic = a.group_magic;
     auto div_g = [&](int x) { return g_magic ? (int)__umulhi((uint32_t)x, g_magic) : x; };
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, Attn
     const int kv_limit = it.prefix_len + div_g(row0 + rows_here - 1) + 1;
     const int ntiles_all = (kv_limit + TN - 1) / TN;
     constexpr int PART = TM * (D + 2);
-    const float* const part0 = static_cast<const float*>(a.partial) + ((long long)(it.split >> 16) * S * Hkv + g) * PART;
+    const float* const part0 = static_cast<const float*>(a.partial) + ((long long)(wl.part_base + lead * S) * Hkv + g) * PART;
     const long long copy_stride = (long long)Hkv * PART;
     const int d4 = threadIdx.x % TPR;
     __bf16* const outp = static_cast<__bf16*>(a.out);
@@ -583,7 +586,10 @@ __global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, Attn
 
 template <int D, int NG, int RING>
 void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+    if (wl.splits > 1)
+        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, true>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+    else
+        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, false>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
 }
 
 }  // namespace

@@ -143,7 +143,7 @@ int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, int group, uint
         if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
         for (int t = 0; t < (int)tiles; ++t)
             plan->items.push_back({ragc::attn_bf16_item_cost(p, n, group, t),
-                                   ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r], 1u << 8}});
+                                   ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
     }
     std::stable_sort(plan->items.begin(), plan->items.end(), [](const Bf16Item& x, const Bf16Item& y) { return x.cost > y.cost; });
     const int64_t wgs = (int64_t)plan->items.size() * pool->kv_heads;
@@ -156,7 +156,7 @@ int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, int group, uint
         splits = (int)std::min<int64_t>(cus / wgs, ragc::kAttnMaxSplits);
         splits = std::min(splits, plan->items.front().cost / 8);
         if (const char* force = std::getenv("RAGC_ATTN_SPLITS")) splits = std::min(std::atoi(force), ragc::kAttnMaxSplits);
-        if (splits < 1 || (int64_t)plan->items.size() * splits > 65535) splits = 1;
+        if (splits < 1) splits = 1;
     }
     plan->splits = splits;
     // With at least two workgroups per CU two 4-wave workgroups share a CU; otherwise one 8-wave
@@ -250,14 +250,13 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     const size_t per_launch = (size_t)ragc::kAttnMaxItems / S;
     for (size_t i = 0; i < plan.items.size(); i += per_launch) {
         ragc::AttnWorkList wl{}, leads{};
+        wl.splits = leads.splits = S;
+        wl.part_base = leads.part_base = (int32_t)(i * S);
         const size_t cnt = std::min(per_launch, plan.items.size() - i);
-        for (size_t j = 0; j < cnt; ++j)
-            for (int c = 0; c < S; ++c) {
-                ragc::AttnItem it = plan.items[i + j].it;
-                it.split = (uint32_t)c | (uint32_t)S << 8 | (uint32_t)(i + j) << 16;
-                wl.item[wl.n++] = it;
-                if (c == 0) leads.item[leads.n++] = it;
-            }
+        for (size_t j = 0; j < cnt; ++j) {
+            for (int c = 0; c < S; ++c) wl.item[wl.n++] = plan.items[i + j].it;
+            leads.item[leads.n++] = plan.items[i + j].it;
+        }
         hipError_t e = ragc::launch_attn_bf16(a, wl, plan.variant, s);
         if (e == hipSuccess && S > 1) e = ragc::launch_attn_bf16_merge(a, leads, s);
         if (e != hipSuccess) return hip_fail(e, "prefill attention launch");

@@ -50,7 +50,7 @@ hipError_t launch_attn_f32(const AttnLaunch& a, hipStream_t s);
 // them in the kernel argument buffer (no device staging); long lists go out in
 // several launches.
 constexpr int kAttnRowsPerItem = 128;
-constexpr int kAttnMaxItems = 160;
+constexpr int kAttnMaxItems = 224;
 // One work item carries the request's lengths, so a workgroup needs no memory round trip
 // before it can look up its first block ids.
 struct AttnItem {
@@ -58,14 +58,17 @@ struct AttnItem {
     int32_t prefix_len;
     int32_t new_len;
     int32_t new_start;
-    uint32_t split;      // copy index | copies << 8 | index of the item among the split items << 16
 };
 // bytes of one partial result: O [rows][D] fp32, then (max, sum) per row
 inline int64_t attn_partial_bytes(int head_dim) { return (int64_t)kAttnRowsPerItem * (head_dim + 2) * 4; }
 constexpr int kAttnMaxSplits = 16;
+// With `splits` = S > 1 every work item appears S times in a row (entry e is copy e % S) and
+// entry e leaves its partial result in slot part_base + e of the workspace.
 struct AttnWorkList {
     int32_t n;
-    int32_t pad[3];
+    int32_t splits;
+    int32_t part_base;
+    int32_t pad;
     AttnItem item[kAttnMaxItems];
 };
 enum AttnVariant {
