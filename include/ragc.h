@@ -127,8 +127,12 @@ const char* ragc_last_error(void);
  * Returns 0 on bad arguments. */
 int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype);
 
-/* Workspace ragc_prefill_attn needs for this batch (bytes, possibly 0).  Only the
- * host arrays of `batch` are read.  Returns a negative ragc_status on error. */
+/* Workspace ragc_prefill_attn needs for this batch with these flags (bytes, possibly 0).
+ * A bf16 batch with fewer (request, 128-row tile, kv head) work items than the GPU has
+ * compute units is split along the keys over several workgroups, whose partial results
+ * (unnormalised output, row max and row sum, fp32) pass through the workspace and are
+ * combined by a second kernel of the same call; RAGC_ATTN_NO_SPLIT turns that off (0 bytes).
+ * Only the host arrays of `batch` are read.  Returns a negative ragc_status on error. */
 int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads,
                                     uint32_t flags);
 
@@ -141,8 +145,11 @@ int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* 
  * rounded to bf16 before the PV product and the output is rounded to nearest even.
  *   q, out        [device] [sum new_len][q_heads][head_dim]
  *   k_new, v_new  [device] [sum new_len][kv_heads][head_dim]
- *   workspace     [device] >= ragc_prefill_attn_workspace() bytes, 256-byte aligned
- *                 (may be NULL when that is 0)
+ *   workspace     [device] >= ragc_prefill_attn_workspace() bytes for the same flags, 256-byte
+ *                 aligned (may be NULL when that is 0; too small: RAGC_ERR_WORKSPACE, nothing is
+ *                 launched).  Contents need no initialisation and are undefined afterwards; it
+ *                 is in use until the call's work has finished on `stream`, so calls on
+ *                 different streams need workspaces of their own.
  * With RAGC_ATTN_APPEND_FUSED the same pass performs ragc_kv_append; the pool then
  * holds byte-identical contents to a separate ragc_kv_append call.
  * Requests with new_len == 0 are skipped.  prefix_len == 0 is plain causal
