@@ -144,6 +144,24 @@ def measure_cost_grid(harness, W, B, torch):
             "t_us": t, "off_grid": check, "max_rel_err": max(c["rel_err"] for c in check)}
 
 
+def measure_decode(harness, W, B, torch):
+    """Decode steps (one new token per request) on the same pool and kernel: the K/V of every
+    request is read once, so the figure of merit is K/V bytes per second against the HBM peak.
+    The same data is read every step (warm in the last-level cache when it fits)."""
+    out = {}
+    for name, R, P, hq, hkv in (("R64_P1024_gqa32/8", 64, 1024, 32, 8), ("R128_P2048_gqa32/8", 128, 2048, 32, 8),
+                                ("R8_P1024_mha32", 8, 1024, 32, 32), ("R4_P4096_gqa64/8", 4, 4096, 64, 8)):
+        w = W.make_small("bf16", hq, hkv, 128, [(P, 1)] * R, seed=3, sigma=0.5)
+        dw = harness.DeviceWorkload(w)
+        _, em = _time_steps(lambda i: dw.attn(B.RAGC_ATTN_APPEND_FUSED), 30, 5, torch)
+        kv = R * (P + 1) * hkv * 128 * 2 * 2
+        out[name] = {"us": em * 1e3, "kv_bytes": kv, "gbs": kv / em / 1e6, "hbm_frac": kv / em / 1e6 / HBM_PEAK_GBS,
+                     "split_workspace_bytes": int(dw.workspace_bytes)}
+        del dw
+    torch.cuda.empty_cache()
+    return out
+
+
 def measure_layer_prefetch(harness, B, torch):
     """One request through 8 layers, each with its own pool: 4096 cached tokens that live in
     pinned host memory (256 blocks per layer to bring in) and 512 new tokens, Mistral-7B head
@@ -341,6 +359,7 @@ def main():
         torch.cuda.empty_cache()
         # the controller side: measured cost model, layer-ahead copies over per-layer pools, tree throughput
         extras["cost_grid"] = measure_cost_grid(harness, W, B, torch)
+        extras["decode"] = measure_decode(harness, W, B, torch)
         extras["layer_prefetch"] = measure_layer_prefetch(harness, B, torch)
         extras["controller"] = measure_controller()
         result["other_workloads"] = extras
