@@ -369,6 +369,17 @@ def test_split_is_chosen_for_a_single_request_and_for_decode_steps(H):
     assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, 0) == 0
 
 
+@pytest.mark.parametrize("variant,splits", [(0, 1), (1, 1), (0, 3), (1, None)])
+def test_long_prefix_walks_several_block_id_windows(H, variant, splits, monkeypatch):
+    """20,000 cached tokens: 313 key tiles, so a wave refills its 64-entry window of block ids
+    several times (and, split along the keys, starts in the middle of the table)."""
+    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
+    if splits is not None:
+        monkeypatch.setenv("RAGC_ATTN_SPLITS", str(splits))
+    w = W.make_small("bf16", 8, 2, 128, [(20000, 40), (9000, 1)], seed=7301, q_gain=3.0)
+    _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+
+
 def test_many_work_items_take_several_launches(H):
     """More (request, row tile) items than fit one kernel-argument work list."""
     lens = [(16 + (i % 5) * 16, 3 + (i % 7)) for i in range(300)]
