@@ -380,6 +380,38 @@ def test_long_prefix_walks_several_block_id_windows(H, variant, splits, monkeypa
     _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_randomised_shapes_match_oracle(H, seed, monkeypatch):
+    """Random head counts (group sizes 1-8, also odd ones), head dims, batch sizes and lengths
+    (empty requests, empty prefixes, single tokens, lengths around tile edges), random kernel
+    variant and number of key copies; output against the oracle and appended pool byte for byte."""
+    import random
+
+    rng = random.Random(9000 + seed)
+    hkv = rng.choice([1, 2, 3, 4, 8])
+    group = rng.choice([1, 2, 3, 4, 5, 7, 8])
+    d = rng.choice([64, 128])
+    edge = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257]
+    lens = []
+    for _ in range(rng.randrange(1, 9)):
+        p = rng.choice([rng.choice(edge), rng.randrange(0, 900), rng.randrange(0, 3000)])
+        n = rng.choice([0, 1, rng.choice(edge), rng.randrange(1, 200), rng.randrange(1, 600 // group + 2)])
+        lens.append((p, n))
+    if all(n == 0 for _, n in lens):
+        lens.append((rng.randrange(0, 300), 5))
+    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(rng.randrange(2)))
+    if rng.random() < 0.6:
+        monkeypatch.setenv("RAGC_ATTN_SPLITS", str(rng.choice([1, 2, 3, 4, 5, 8, 16])))
+    # values ~ N(0,1) * 0.5 as in the benchmark configurations: with a sharp softmax |O| reaches max |V|, and
+    # above 2 the bf16 output grid itself is 2^-6 wide or more, which leaves the 2e-2 gate no room
+    w = W.make_small("bf16", hkv * group, hkv, d, lens, seed=9100 + seed, sigma=0.5, q_gain=rng.choice([1.0, 2.0, 8.0]))
+    dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    pk, pv = w.pool_image()
+    OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
+    assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
+    assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
+
+
 def test_many_work_items_take_several_launches(H):
     """More (request, row tile) items than fit one kernel-argument work list."""
     lens = [(16 + (i % 5) * 16, 3 + (i % 7)) for i in range(300)]
