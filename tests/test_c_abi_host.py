@@ -94,6 +94,27 @@ def test_attention_argument_errors(lib):
     assert _attn_code(_pool(), b6) == B.RAGC_ERR_NULL
 
 
+def test_size_limits_and_workspace_errors(lib):
+    many, keep = _batch(p=(0,) * 65536, n=(1,) * 65536, stride=1)
+    assert _attn_code(_pool(), many) == B.RAGC_ERR_SHAPE  # more requests than a work item can name
+    huge, keep2 = _batch(p=(0,), n=(2_000_000,), stride=125_000)
+    assert _attn_code(_pool(), huge, hq=16) == B.RAGC_ERR_RANGE  # 16 M rows: more than 65535 row tiles
+    assert "too large" in B.ragc_last_error()
+    # one request with a long prefix is split along its keys: the workspace is then mandatory
+    one, keep3 = _batch(p=(4096,), n=(16,), stride=300)
+    need = B.ragc_prefill_attn_workspace(_pool(num_blocks=512), one, 8)
+    assert need > 0 and need % (128 * (128 + 2) * 4) == 0
+    assert B.ragc_prefill_attn_workspace(_pool(num_blocks=512), one, 8, B.RAGC_ATTN_NO_SPLIT) == 0
+    assert B.ragc_prefill_attn_workspace(_pool(num_blocks=512, dtype=B.RAGC_DTYPE_F32), one, 8) == 0
+    for ws, nbytes, code in ((None, 0, B.RAGC_ERR_WORKSPACE), (A, need - 1, B.RAGC_ERR_WORKSPACE), (A + 16, need, B.RAGC_ERR_ALIGN)):
+        with pytest.raises(B.RagcError) as e:
+            B.ragc_prefill_attn(_pool(num_blocks=512), one, A, A, A, A, 8, 0.1, 0, ws, nbytes)
+        assert e.value.code == code
+    with pytest.raises(B.RagcError) as e:
+        B.ragc_prefill_attn_workspace(_pool(num_blocks=512), one, 3)
+    assert e.value.code == B.RAGC_ERR_SHAPE
+
+
 def test_empty_work_returns_ok_without_a_device(lib):
     b, keep = _batch(p=(10, 3), n=(0, 0))
     assert B.ragc_prefill_attn(_pool(), b, None, None, None, None, 8, 0.1) == 0
