@@ -29,10 +29,10 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_f32_kernel(AttnLaunch a) {
-    __shared__ float Ks[KC][D + 1];
-    __shared__ float Vs[KC][D];
-    __shared__ float Qs[TR][D];
-    __shared__ float Ps[4][KC];
+    __shared__ __attribute__((aligned(16))) float Ks[KC][D + 4];  // rows padded by one 16-byte chunk: 16-byte reads of 16 keys hit all banks
+    __shared__ __attribute__((aligned(16))) float Vs[KC][D];
+    __shared__ __attribute__((aligned(16))) float Qs[TR][D];
+    __shared__ __attribute__((aligned(16))) float Ps[4][KC][4];  // per wave: p of its 4 rows, per key
 
     const int r = blockIdx.z;
     const int h = blockIdx.y;
@@ -103,42 +103,59 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnLaunch a) {
                     vv = *reinterpret_cast<const float4*>(v_new + off);
                 }
             }
-            Ks[row][c4 * 4 + 0] = kk.x;
-            Ks[row][c4 * 4 + 1] = kk.y;
-            Ks[row][c4 * 4 + 2] = kk.z;
-            Ks[row][c4 * 4 + 3] = kk.w;
+            *reinterpret_cast<float4*>(&Ks[row][c4 * 4]) = kk;
             *reinterpret_cast<float4*>(&Vs[row][c4 * 4]) = vv;
         }
         __syncthreads();
 
+        // scores of the wave's 4 rows at once: lane = (key, half of the head dim); every K chunk read
+        // from LDS serves the 4 rows.  Rows past the end carry q = 0 and are never stored; a row
+        // whose visible keys all lie in earlier chunks gets p = 0 and alpha = 1 below.
+        const int key = lane & 31, dh = lane >> 5;
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int d4 = 0; d4 < D / 8; ++d4) {
+            const float4 kk = *reinterpret_cast<const float4*>(&Ks[key][dh * (D / 2) + d4 * 4]);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const float4 qq = *reinterpret_cast<const float4*>(&Qs[w * 4 + rr][dh * (D / 2) + d4 * 4]);
+                part[rr] += qq.x * kk.x + qq.y * kk.y + qq.z * kk.z + qq.w * kk.w;
+            }
+        }
+        float alpha[4];
+        float4 p4;
+        float* pp = reinterpret_cast<float*>(&p4);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const int il = w * 4 + rr;
-            if (il >= rows) continue;
-            const int visible = P + t0 + il + 1;  // keys [0, visible): prefix, earlier new tokens, itself
-            if (c0 >= visible) continue;
-            // scores: lane handles key (lane & 31) and one half of the head dim
-            const int key = lane & 31, dh = lane >> 5;
-            float part = 0.f;
-#pragma unroll 8
-            for (int d = 0; d < D / 2; ++d) part += Qs[il][dh * (D / 2) + d] * Ks[key][dh * (D / 2) + d];
-            float s = (part + __shfl_xor(part, 32, 64)) * a.scale_log2e;
-            if (c0 + key >= visible) s = -INFINITY;
-            const float m_new = fmaxf(m[rr], wave_max(s));
-            const float alpha = exp2f(m[rr] - m_new);  // first chunk: exp2(-inf) = 0
-            const float p = exp2f(s - m_new);
-            l[rr] = l[rr] * alpha + wave_sum(dh == 0 ? p : 0.f);
+            const int visible = P + t0 + w * 4 + rr + 1;  // keys [0, visible): prefix, earlier new tokens, itself
+            float sc = (part[rr] + __shfl_xor(part[rr], 32, 64)) * a.scale_log2e;
+            if (c0 + key >= visible) sc = -INFINITY;
+            const float m_new = fmaxf(m[rr], wave_max(sc));
+            alpha[rr] = exp2f(m[rr] - m_new);  // first chunk: exp2(-inf) = 0
+            pp[rr] = exp2f(sc - m_new);
+            l[rr] = l[rr] * alpha[rr] + wave_sum(dh == 0 ? pp[rr] : 0.f);
             m[rr] = m_new;
-            __builtin_amdgcn_wave_barrier();
-            if (dh == 0) Ps[w][key] = p;
-            __builtin_amdgcn_wave_barrier();
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (dh == 0) *reinterpret_cast<float4*>(&Ps[w][key][0]) = p4;
+        __builtin_amdgcn_wave_barrier();
+        // O += P V: lane = column of V; every V element read from LDS serves the 4 rows
 #pragma unroll
-            for (int dd = 0; dd < D / 64; ++dd) {
-                float acc = o[rr][dd] * alpha;
+        for (int dd = 0; dd < D / 64; ++dd) {
+            float acc[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) acc[rr] = o[rr][dd] * alpha[rr];
 #pragma unroll 8
-                for (int j = 0; j < KC; ++j) acc += Ps[w][j] * Vs[j][lane + 64 * dd];
-                o[rr][dd] = acc;
+            for (int j = 0; j < KC; ++j) {
+                const float v = Vs[j][lane + 64 * dd];
+                const float4 pj = *reinterpret_cast<const float4*>(&Ps[w][j][0]);
+                acc[0] += pj.x * v;
+                acc[1] += pj.y * v;
+                acc[2] += pj.z * v;
+                acc[3] += pj.w * v;
             }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) o[rr][dd] = acc[rr];
         }
     }
 
