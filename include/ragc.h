@@ -18,8 +18,13 @@
  *     observed through the stream.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - Pointers are marked [device], [host] or [pinned host].
- *   - Every entry point returns 0 or a negative ragc_status.  On error nothing has
- *     been enqueued.  ragc_last_error() gives a thread-local message.
+ *   - Every entry point returns 0 or a negative ragc_status.  Every check runs on the
+ *     host before the first launch, so an argument error enqueues nothing.  The one
+ *     exception: a batch with more work items than one launch carries goes out in
+ *     several launches, and if the runtime refuses a later one (RAGC_ERR_HIP) the
+ *     earlier ones stay enqueued; `out` and, with the fused append, the pool blocks of
+ *     the new tokens are then partly written.  ragc_last_error() gives a thread-local
+ *     message.
  *   - Block size is 16 tokens.  head_dim is 64 or 128.  dtype is fp32 or bf16 and is
  *     the type of the pool, of q/k_new/v_new and of the output.
  *
@@ -34,12 +39,48 @@
  *   prefix_len[r] are the cached documents (read only); positions from
  *   prefix_len[r] on are the request's new tokens (written by the append).
  *
- * Preconditions the library cannot check on the device side
+ * Preconditions the kernels themselves cannot check
  *   - every block that receives new tokens belongs to that request alone (shared
  *     chains cover only full blocks inside the prefix);
  *   - block_table rows hold ceil((prefix_len+new_len)/16) valid block ids;
+ *   - the device arrays of a batch equal their host copies;
  *   - no swap writes a block that a running attention call reads.
- *   When host mirrors of the tables are passed they ARE checked.
+ *   Block ids are range-checked whenever h_block_table is given.  The first three are
+ *   checked in full by ragc_batch_validate / RAGC_ATTN_VALIDATE (a debug mode: it reads
+ *   the device arrays back synchronously).  The last one is the caller's stream order.
+ *
+ * Accuracy (bf16).  Against exact arithmetic on the same bf16 inputs the output is
+ *   within 2e-2 absolute wherever |out| < 8; from 8 on, half a unit of the bf16 output
+ *   grid alone is 2^-5 or more and the bound becomes 2^-8 * |out| + 4e-3.  fp32: 1e-4.
+ *
+ * Several layers, one pool per layer (Sec. 5.1 "Swap out only once": transfers overlap
+ *   with computation).  The library keeps no state, so the caller orders the calls.  All
+ *   layers share block ids and host slots; a request's plan (swap-out pairs, swap-in
+ *   pairs, table row) applies to each.  The order that overlaps copies with attention:
+ *     main stream:  record event `begun`
+ *     side stream:  wait `begun` (the copies may touch blocks that earlier work on the
+ *                   main stream still reads or appends); then for every layer l in turn:
+ *                   ragc_kv_swap(TO_HOST, out pairs), ragc_kv_swap(TO_DEVICE, in pairs),
+ *                   record event ready[l].  Outgoing before incoming, because an
+ *                   incoming block may reuse the device block an outgoing one frees.
+ *     main stream:  for every layer l in turn: wait ready[l];
+ *                   ragc_prefill_attn(pool of l, RAGC_ATTN_APPEND_FUSED)
+ *     afterwards:   the side stream waits for the main stream before the next request's
+ *                   copies (they may evict what this request appended).
+ *   The side stream therefore runs ahead of the main one by as many layers as the copies
+ *   are faster than attention; the main stream waits for its own layer only.  One
+ *   workspace serves all layers, since their attention calls share a stream.
+ *
+ * Where this header departs from the three-call sketch of the benchmark spec
+ *   (ragc_prefill_attn, ragc_kv_append, ragc_kv_swap with descriptors of device pointers
+ *   and optional host mirrors):
+ *   - ragc_kv_swap takes two more arguments: num_host_slots (so host slot ids can be
+ *     range-checked) and flags (copy mechanism).
+ *   - the fused-append flag is spelled RAGC_ATTN_APPEND_FUSED; RAGC_ATTN_NO_SPLIT is new.
+ *   - more exports: ragc_last_error, ragc_kv_bytes_per_token, ragc_prefill_attn_workspace,
+ *     ragc_batch_validate, ragc_debug_set_attn_plan.
+ *   - host copies of the lengths are optional but their absence costs a synchronous
+ *     read-back per call (the launch is sized on the host).
  */
 #ifndef RAGC_H
 #define RAGC_H
@@ -87,10 +128,13 @@ typedef struct ragc_kv_pool {
  * starting at 0.  ragc_prefill_attn accepts any offsets (so a subset of a batch
  * can be launched over the same packed tensors); ragc_kv_append needs
  * new_start[r+1] = new_start[r] + new_len[r] (new_start[0] may be non-zero).
- * The h_* arrays are host copies of the same metadata: h_prefix_len, h_new_len and
- * h_new_start are required (the launch is sized from them and the work items carry
- * them to the device in the kernel arguments); h_block_table is optional and, when
- * given, every entry the call will touch is range-checked. */
+ * The h_* arrays are host copies of the same metadata.  The launch is sized on the host
+ * and the work items carry the lengths to the device in the kernel arguments, so a
+ * serving loop passes h_prefix_len, h_new_len and h_new_start; any of them that is NULL
+ * is read back from its device array with a synchronous hipMemcpy inside the call (slow,
+ * not capturable in a HIP graph, and the device array must be complete by then).
+ * h_block_table is optional; when given, every entry the call will touch is
+ * range-checked. */
 typedef struct ragc_batch {
     int32_t num_reqs;
     int32_t table_stride;          /* entries per block_table row */
@@ -107,6 +151,7 @@ typedef struct ragc_batch {
 /* flags of ragc_prefill_attn */
 #define RAGC_ATTN_APPEND_FUSED 0x1u /* also write k_new/v_new into their paged slots */
 #define RAGC_ATTN_NO_SPLIT 0x2u     /* never split the key range across workgroups */
+#define RAGC_ATTN_VALIDATE 0x4u     /* debug: run ragc_batch_validate first (synchronous read-backs) */
 
 /* flags of ragc_kv_swap */
 #define RAGC_SWAP_AUTO 0x0u
@@ -126,6 +171,24 @@ const char* ragc_last_error(void);
  * head_dim * sizeof(dtype) (the KV Size column of the paper's model table).
  * Returns 0 on bad arguments. */
 int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype);
+
+/* Debug validation of the preconditions that the kernels cannot check (see the top of
+ * this file): reads prefix_len, new_len, new_start and block_table back from the device
+ * (synchronous copies; the arrays must be complete), compares them with the host copies
+ * that are given, range-checks every table entry the batch touches and, with
+ * writes_new_tokens != 0 (a fused or standalone append follows), requires that every
+ * block that receives new tokens does so for one request only and is in no request's
+ * read-only prefix.  Returns RAGC_ERR_RANGE with a message that names the block and the
+ * requests.  Not for the serving path. */
+int ragc_batch_validate(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t writes_new_tokens);
+
+/* Test hook: override how ragc_prefill_attn lays a bf16 batch out on the GPU.
+ *   variant  -1 = library's choice, 0 = 4-wave workgroups, 1 = 8-wave workgroups
+ *   splits    0 = library's choice, 1..16 = copies of every work item along the keys
+ * Process-wide and not synchronised with calls in flight on other threads: set it
+ * before the calls it should affect and reset it (-1, 0) afterwards.  It changes the
+ * workspace size, so query ragc_prefill_attn_workspace under the same setting. */
+int ragc_debug_set_attn_plan(int32_t variant, int32_t splits);
 
 /* Workspace ragc_prefill_attn needs for this batch with these flags (bytes, possibly 0).
  * A bf16 batch with fewer (request, 128-row tile, kv head) work items than the GPU has
@@ -160,7 +223,9 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
 
 /* Write the fresh K/V of every request into its paged slots (Sec. 4: the tensors
  * of the accessed documents are cached after the first token): row
- * new_start[r]+i of k_new/v_new goes to position prefix_len[r]+i.  A byte copy. */
+ * new_start[r]+i of k_new/v_new goes to position prefix_len[r]+i.  A byte copy.
+ * Rows must be packed in request order, new_start[r+1] = new_start[r] + new_len[r]
+ * (RAGC_ERR_RANGE otherwise; new_start[0] may be non-zero). */
 int ragc_kv_append(const ragc_kv_pool* pool, const ragc_batch* batch, const void* k_new, const void* v_new,
                    void* stream);
 

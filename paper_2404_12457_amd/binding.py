@@ -19,12 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libragc.so")
 RAGC_OK = 0
 RAGC_ERR_NULL, RAGC_ERR_SHAPE, RAGC_ERR_RANGE, RAGC_ERR_ALIGN, RAGC_ERR_HIP, RAGC_ERR_WORKSPACE = -1, -2, -3, -4, -5, -6
 RAGC_DTYPE_F32, RAGC_DTYPE_BF16 = 0, 1
-RAGC_ATTN_APPEND_FUSED, RAGC_ATTN_NO_SPLIT = 0x1, 0x2
+RAGC_ATTN_APPEND_FUSED, RAGC_ATTN_NO_SPLIT, RAGC_ATTN_VALIDATE = 0x1, 0x2, 0x4
 RAGC_SWAP_AUTO, RAGC_SWAP_MEMCPY, RAGC_SWAP_KERNEL = 0, 1, 2
 RAGC_SWAP_TO_DEVICE, RAGC_SWAP_TO_HOST = 0, 1
 
 EXPORTS = ["ragc_version", "ragc_last_error", "ragc_kv_bytes_per_token", "ragc_prefill_attn_workspace",
-           "ragc_prefill_attn", "ragc_kv_append", "ragc_kv_swap", "ragc_kv_gather"]
+           "ragc_prefill_attn", "ragc_kv_append", "ragc_kv_swap", "ragc_kv_gather",
+           "ragc_batch_validate", "ragc_debug_set_attn_plan"]
 
 
 class ragc_kv_pool(ctypes.Structure):
@@ -65,6 +66,10 @@ def load() -> ctypes.CDLL:
         lib.ragc_prefill_attn_workspace.argtypes = [P, P, I32, U32]
         lib.ragc_prefill_attn.restype = ctypes.c_int
         lib.ragc_prefill_attn.argtypes = [P, P, P, P, P, P, I32, ctypes.c_float, U32, P, ctypes.c_size_t, P]
+        lib.ragc_batch_validate.restype = ctypes.c_int
+        lib.ragc_batch_validate.argtypes = [P, P, I32]
+        lib.ragc_debug_set_attn_plan.restype = ctypes.c_int
+        lib.ragc_debug_set_attn_plan.argtypes = [I32, I32]
         lib.ragc_kv_append.restype = ctypes.c_int
         lib.ragc_kv_append.argtypes = [P, P, P, P, P]
         lib.ragc_kv_swap.restype = ctypes.c_int
@@ -129,6 +134,14 @@ def ragc_prefill_attn(pool, batch, q, k_new, v_new, out, q_heads: int, softmax_s
                       workspace=None, workspace_bytes: int = 0, stream: int = 0) -> int:
     return _check(load().ragc_prefill_attn(_ref(pool), _ref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), q_heads,
                                            softmax_scale, flags, _ptr(workspace), workspace_bytes, stream or None))
+
+
+def ragc_batch_validate(pool, batch, writes_new_tokens: bool = True) -> int:
+    return _check(load().ragc_batch_validate(_ref(pool), _ref(batch), 1 if writes_new_tokens else 0))
+
+
+def ragc_debug_set_attn_plan(variant: int = -1, splits: int = 0) -> int:
+    return _check(load().ragc_debug_set_attn_plan(variant, splits))
 
 
 def ragc_kv_append(pool, batch, k_new, v_new, stream: int = 0) -> int:

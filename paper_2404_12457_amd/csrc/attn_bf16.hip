@@ -334,15 +334,20 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         // a row that has not seen a key yet (possible in the second wave group) has m_run = -inf
         // and only masked scores: subtract 0 instead, so that exp2(-inf - 0) = 0 and not NaN
         const float m_sub = m_run == -INFINITY ? 0.f : m_run;
+        // The row sum is taken over the bf16-rounded probabilities, the same weights the PV
+        // product uses, so that the rounding of P cancels between numerator and denominator.
         float psum = 0.f;
         bf16x8 pb[2][2];
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(sacc[sub][i] * c - m_sub);
-                psum += p;
-                pb[sub][i >> 3][i & 7] = (__bf16)p;
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(sacc[sub][i] * c - m_sub);
+                const float p1 = __builtin_amdgcn_exp2f(sacc[sub][i + 1] * c - m_sub);
+                const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pp, kOnes2, psum, false);
+                pb[sub][i >> 3][i & 7] = pp[0];
+                pb[sub][i >> 3][(i & 7) + 1] = pp[1];
             }
         l_run += psum;
 

@@ -9,6 +9,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -16,6 +17,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int TN = 64;                    // keys per LDS tile
 constexpr float kRescaleThreshold = 8.f;  // log2 units
+constexpr bf16x2 kOnes2 = {(__bf16)1.0f, (__bf16)1.0f};
 
 // Wave-wide copy of 64 x 16 bytes from global memory straight into LDS: lane i's 16 bytes
 // land at lds_addr + 16*i.  Issued as inline assembly on purpose: the compiler's own

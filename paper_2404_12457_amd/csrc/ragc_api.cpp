@@ -3,6 +3,7 @@
 #include "../../include/ragc.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -14,6 +15,9 @@
 
 namespace {
 thread_local char g_err[512] = "";
+// test overrides of the launch plan (ragc_debug_set_attn_plan); -1 / 0 = the library decides
+std::atomic<int> g_force_variant{-1};
+std::atomic<int> g_force_splits{0};
 }
 
 namespace ragc {
@@ -56,25 +60,71 @@ struct BatchInfo {
     int32_t max_new = 0;
 };
 
+// Host view of the batch metadata.  The h_* arrays of the batch are used when given; an array
+// that is missing is read back from its device copy (a synchronous copy, the slow path).
+struct HostMeta {
+    const int32_t* prefix_len = nullptr;
+    const int32_t* new_len = nullptr;
+    const int32_t* new_start = nullptr;
+    const int32_t* block_table = nullptr;  // may stay NULL: then block ids are not range-checked
+    std::vector<int32_t> own_prefix, own_new, own_start, own_table;
+};
+
+int hip_fail(hipError_t e, const char* what) { return fail(RAGC_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
+
+int read_back(std::vector<int32_t>* dst, const int32_t* dev, size_t n, const char* what) {
+    if (!dev) return fail(RAGC_ERR_NULL, "%s: neither the host copy nor the device array is given", what);
+    dst->resize(n);
+    const hipError_t e = hipMemcpy(dst->data(), dev, n * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, what);
+    return RAGC_OK;
+}
+
+// want_table: read the block table back as well when no host copy is given (validation mode).
+int resolve_host(const ragc_batch* b, bool want_table, HostMeta* h) {
+    const size_t R = (size_t)b->num_reqs;
+    h->prefix_len = b->h_prefix_len;
+    h->new_len = b->h_new_len;
+    h->new_start = b->h_new_start;
+    h->block_table = b->h_block_table;
+    if (!h->prefix_len) {
+        if (int rc = read_back(&h->own_prefix, b->prefix_len, R, "prefix_len")) return rc;
+        h->prefix_len = h->own_prefix.data();
+    }
+    if (!h->new_len) {
+        if (int rc = read_back(&h->own_new, b->new_len, R, "new_len")) return rc;
+        h->new_len = h->own_new.data();
+    }
+    if (!h->new_start) {
+        if (int rc = read_back(&h->own_start, b->new_start, R, "new_start")) return rc;
+        h->new_start = h->own_start.data();
+    }
+    if (!h->block_table && want_table) {
+        if (b->table_stride <= 0) return fail(RAGC_ERR_SHAPE, "table_stride %d", b->table_stride);
+        if (int rc = read_back(&h->own_table, b->block_table, R * (size_t)b->table_stride, "block_table")) return rc;
+        h->block_table = h->own_table.data();
+    }
+    return RAGC_OK;
+}
+
 // Host-side checks of the batch metadata.  need_device: the device arrays are required.
-int check_batch(const ragc_kv_pool* pool, const ragc_batch* b, bool need_device, BatchInfo* info) {
+int check_batch(const ragc_kv_pool* pool, const ragc_batch* b, bool need_device, bool want_table, HostMeta* h, BatchInfo* info) {
     if (!b) return fail(RAGC_ERR_NULL, "batch is NULL");
     if (b->num_reqs < 0 || b->num_reqs > 65535) return fail(RAGC_ERR_SHAPE, "num_reqs %d", b->num_reqs);
     if (b->num_reqs == 0) return RAGC_OK;
-    if (!b->h_prefix_len || !b->h_new_len || !b->h_new_start)
-        return fail(RAGC_ERR_NULL, "h_prefix_len / h_new_len / h_new_start (host copies) are required");
     if (need_device && (!b->prefix_len || !b->new_len || !b->new_start || !b->block_table))
         return fail(RAGC_ERR_NULL, "a device array of the batch is NULL");
     if (b->table_stride <= 0) return fail(RAGC_ERR_SHAPE, "table_stride %d", b->table_stride);
+    if (int rc = resolve_host(b, want_table, h)) return rc;
     for (int r = 0; r < b->num_reqs; ++r) {
-        const int64_t p = b->h_prefix_len[r], n = b->h_new_len[r];
+        const int64_t p = h->prefix_len[r], n = h->new_len[r];
         if (p < 0 || n < 0) return fail(RAGC_ERR_RANGE, "request %d: prefix_len %lld, new_len %lld", r, (long long)p, (long long)n);
-        if (b->h_new_start[r] < 0) return fail(RAGC_ERR_RANGE, "request %d: new_start %d", r, b->h_new_start[r]);
+        if (h->new_start[r] < 0) return fail(RAGC_ERR_RANGE, "request %d: new_start %d", r, h->new_start[r]);
         const int64_t blocks = (p + n + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE;
         if (blocks > b->table_stride)
             return fail(RAGC_ERR_RANGE, "request %d: %lld tokens need %lld table entries, table_stride is %d", r, (long long)(p + n), (long long)blocks, b->table_stride);
-        if (b->h_block_table) {
-            const int32_t* row = b->h_block_table + (int64_t)r * b->table_stride;
+        if (h->block_table) {
+            const int32_t* row = h->block_table + (int64_t)r * b->table_stride;
             for (int64_t i = 0; i < blocks; ++i)
                 if (row[i] < 0 || row[i] >= pool->num_blocks)
                     return fail(RAGC_ERR_RANGE, "request %d: block_table[%lld] = %d outside [0, %d)", r, (long long)i, row[i], pool->num_blocks);
@@ -83,6 +133,68 @@ int check_batch(const ragc_kv_pool* pool, const ragc_batch* b, bool need_device,
         info->max_new = std::max<int32_t>(info->max_new, (int32_t)n);
     }
     if (info->total_new > (int64_t)1 << 30) return fail(RAGC_ERR_RANGE, "sum of new_len %lld too large", (long long)info->total_new);
+    return RAGC_OK;
+}
+
+// new_start must be the running sum of new_len (what the append kernel's row search assumes)
+int check_packed(const ragc_batch* b, const HostMeta& h) {
+    for (int r = 0; r + 1 < b->num_reqs; ++r)
+        if ((int64_t)h.new_start[r + 1] != (int64_t)h.new_start[r] + h.new_len[r])
+            return fail(RAGC_ERR_RANGE, "request %d: new_start[%d] = %d, expected new_start[%d] + new_len[%d] = %lld (rows must be packed in request order)",
+                        r + 1, r + 1, h.new_start[r + 1], r, r, (long long)h.new_start[r] + h.new_len[r]);
+    return RAGC_OK;
+}
+
+// Debug validation of what the device side cannot check: the device arrays equal their host
+// copies, and (writes = true) every block that receives new tokens appears once, in one
+// request, and in no request's read-only prefix.
+int validate_batch(const ragc_kv_pool* pool, const ragc_batch* b, const HostMeta& h, bool writes) {
+    const size_t R = (size_t)b->num_reqs;
+    std::vector<int32_t> dev;
+    struct { const int32_t* host; const int32_t* device; size_t n; const char* name; } arrays[] = {
+        {b->h_prefix_len, b->prefix_len, R, "prefix_len"},
+        {b->h_new_len, b->new_len, R, "new_len"},
+        {b->h_new_start, b->new_start, R, "new_start"},
+    };
+    for (auto& a : arrays) {
+        if (!a.host || !a.device) continue;  // nothing to compare (a missing host copy was read from the device anyway)
+        if (int rc = read_back(&dev, a.device, a.n, a.name)) return rc;
+        for (size_t i = 0; i < a.n; ++i)
+            if (dev[i] != a.host[i]) return fail(RAGC_ERR_RANGE, "%s[%zu]: device copy %d differs from host copy %d", a.name, i, dev[i], a.host[i]);
+    }
+    if (b->h_block_table && b->block_table) {
+        if (int rc = read_back(&dev, b->block_table, R * (size_t)b->table_stride, "block_table")) return rc;
+        for (size_t r = 0; r < R; ++r) {
+            const int64_t blocks = ((int64_t)h.prefix_len[r] + h.new_len[r] + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE;
+            for (int64_t i = 0; i < blocks; ++i) {
+                const size_t at = r * (size_t)b->table_stride + (size_t)i;
+                if (dev[at] != b->h_block_table[at])
+                    return fail(RAGC_ERR_RANGE, "block_table[%zu][%lld]: device copy %d differs from host copy %d", r, (long long)i, dev[at], b->h_block_table[at]);
+            }
+        }
+    }
+    if (!writes || !h.block_table) return RAGC_OK;
+    // owner[block]: -1 untouched, r >= 0: receives new tokens of request r, -2: read as prefix by some request
+    std::vector<int32_t> owner((size_t)pool->num_blocks, -1);
+    for (size_t r = 0; r < R; ++r) {  // pass 1: write targets
+        const int64_t p = h.prefix_len[r], n = h.new_len[r];
+        if (n == 0) continue;
+        const int32_t* row = h.block_table + r * (size_t)b->table_stride;
+        for (int64_t i = p / RAGC_BLOCK_SIZE; i < (p + n + RAGC_BLOCK_SIZE - 1) / RAGC_BLOCK_SIZE; ++i) {
+            if (owner[row[i]] != -1)
+                return fail(RAGC_ERR_RANGE, "block %d receives new tokens of request %zu (table entry %lld) and of request %d: append targets must be exclusive",
+                            row[i], r, (long long)i, owner[row[i]]);
+            owner[row[i]] = (int32_t)r;
+        }
+    }
+    for (size_t r = 0; r < R; ++r) {  // pass 2: read-only prefix blocks (whole blocks below the first write target)
+        const int32_t* row = h.block_table + r * (size_t)b->table_stride;
+        const int64_t full = (h.new_len[r] == 0 ? ((int64_t)h.prefix_len[r] + RAGC_BLOCK_SIZE - 1) : (int64_t)h.prefix_len[r]) / RAGC_BLOCK_SIZE;
+        for (int64_t i = 0; i < full; ++i)
+            if (owner[row[i]] >= 0)
+                return fail(RAGC_ERR_RANGE, "block %d is read as cached prefix by request %zu (table entry %lld) and receives new tokens of request %d",
+                            row[i], r, (long long)i, owner[row[i]]);
+    }
     return RAGC_OK;
 }
 
@@ -116,10 +228,6 @@ int cu_count() {
     return cus;
 }
 
-int hip_fail(hipError_t e, const char* what) {
-    return fail(RAGC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-}
-
 // How the bf16 path will run a batch: the (request, 128-row tile) work items, most key tiles
 // first so the long ones start early; how many copies of each item share its keys; which
 // kernel shape; and the workspace the copies need.  ragc_prefill_attn_workspace and
@@ -135,84 +243,84 @@ struct Bf16Plan {
     int64_t workspace = 0;
 };
 
-int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, int group, uint32_t flags, Bf16Plan* plan) {
+int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, const HostMeta& h, int group, uint32_t flags, Bf16Plan* plan) {
     for (int r = 0; r < batch->num_reqs; ++r) {
-        const int n = batch->h_new_len[r], p = batch->h_prefix_len[r];
+        const int n = h.new_len[r], p = h.prefix_len[r];
         const int64_t rows = (int64_t)n * group;
         const int64_t tiles = (rows + ragc::kAttnRowsPerItem - 1) / ragc::kAttnRowsPerItem;
         if (tiles > 65535) return fail(RAGC_ERR_RANGE, "request %d: new_len * group too large", r);
         for (int t = 0; t < (int)tiles; ++t)
             plan->items.push_back({ragc::attn_bf16_item_cost(p, n, group, t),
-                                   ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, batch->h_new_start[r]}});
+                                   ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, h.new_start[r]}});
     }
     std::stable_sort(plan->items.begin(), plan->items.end(), [](const Bf16Item& x, const Bf16Item& y) { return x.cost > y.cost; });
     const int64_t wgs = (int64_t)plan->items.size() * pool->kv_heads;
     const int64_t cus = cu_count();
     // Fewer work items than CUs: split each along its keys until every CU has one, keeping at
     // least eight key tiles per copy of the longest item (a copy costs about as much as ten tiles
-    // before its first and after its last one).  RAGC_ATTN_SPLITS overrides (tests).
+    // before its first and after its last one).  ragc_debug_set_attn_plan overrides (tests).
     int splits = 1;
     if (!(flags & RAGC_ATTN_NO_SPLIT) && wgs > 0) {
         splits = (int)std::min<int64_t>(cus / wgs, ragc::kAttnMaxSplits);
         splits = std::min(splits, plan->items.front().cost / 8);
-        if (const char* force = std::getenv("RAGC_ATTN_SPLITS")) splits = std::min(std::atoi(force), ragc::kAttnMaxSplits);
+        if (const int force = g_force_splits.load(std::memory_order_relaxed); force > 0) splits = std::min(force, ragc::kAttnMaxSplits);
         if (splits < 1) splits = 1;
     }
     plan->splits = splits;
     // With at least two workgroups per CU two 4-wave workgroups share a CU; otherwise one 8-wave
-    // workgroup divides its key tiles between two wave groups.  RAGC_ATTN_VARIANT overrides (tests).
+    // workgroup divides its key tiles between two wave groups.  ragc_debug_set_attn_plan overrides (tests).
     plan->variant = wgs * splits >= 2 * cus ? ragc::kAttnVariantOneGroup : ragc::kAttnVariantTwoGroups;
-    if (const char* force = std::getenv("RAGC_ATTN_VARIANT")) plan->variant = std::atoi(force);
-    if (plan->variant < 0 || plan->variant >= ragc::kAttnVariantCount)
-        return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VARIANT %d unknown", plan->variant);
+    if (const int force = g_force_variant.load(std::memory_order_relaxed); force >= 0) plan->variant = force;
     plan->workspace = splits > 1 ? (int64_t)plan->items.size() * splits * pool->kv_heads * ragc::attn_partial_bytes(pool->head_dim) : 0;
     return 0;
 }
 
-}  // namespace
+constexpr uint32_t kAttnFlags = RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT | RAGC_ATTN_VALIDATE;
 
-extern "C" {
-
-int ragc_version(void) { return 100; }
-
-const char* ragc_last_error(void) { return g_err; }
-
-int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype) {
-    const int es = esize_of(dtype);
-    if (layers <= 0 || kv_heads <= 0 || head_dim <= 0 || es == 0) return 0;
-    return (int64_t)2 * layers * kv_heads * head_dim * es;
+// Enqueue the launches of a planned bf16 batch: every copy of an item is a list entry of its
+// own and a launch takes kAttnMaxItems entries, so a long list goes out in several launches
+// (each followed by its merge pass when the items are split).
+int run_bf16_plan(ragc::AttnLaunch& a, const Bf16Plan& plan, hipStream_t s) {
+    const int S = plan.splits;
+    const size_t per_launch = (size_t)ragc::kAttnMaxItems / S;
+    for (size_t i = 0; i < plan.items.size(); i += per_launch) {
+        ragc::AttnWorkList wl{}, leads{};
+        wl.splits = leads.splits = S;
+        wl.part_base = leads.part_base = (int32_t)(i * S);
+        const size_t cnt = std::min(per_launch, plan.items.size() - i);
+        for (size_t j = 0; j < cnt; ++j) {
+            for (int c = 0; c < S; ++c) wl.item[wl.n++] = plan.items[i + j].it;
+            leads.item[leads.n++] = plan.items[i + j].it;
+        }
+        hipError_t e = ragc::launch_attn_bf16(a, wl, plan.variant, s);
+        if (e == hipSuccess && S > 1) e = ragc::launch_attn_bf16_merge(a, leads, s);
+        if (e != hipSuccess)
+            return fail(RAGC_ERR_HIP, "prefill attention launch %zu of %zu: %s (earlier launches of this call stay enqueued)",
+                        i / per_launch + 1, (plan.items.size() + per_launch - 1) / per_launch, hipGetErrorString(e));
+    }
+    return RAGC_OK;
 }
 
-int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads, uint32_t flags) {
-    g_err[0] = 0;
-    if (int rc = check_pool(pool)) return rc;
-    if (flags & ~(RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT)) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
-    if (q_heads <= 0 || q_heads % pool->kv_heads != 0)
-        return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
-    BatchInfo info;
-    if (int rc = check_batch(pool, batch, false, &info)) return rc;
-    if (pool->dtype != RAGC_DTYPE_BF16 || batch->num_reqs == 0 || info.total_new == 0) return 0;
-    Bf16Plan plan;
-    if (int rc = plan_bf16(pool, batch, q_heads / pool->kv_heads, flags, &plan)) return rc;
-    return plan.workspace;
-}
-
-int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+int prefill_attn_impl(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
                       void* workspace, size_t workspace_bytes, void* stream) {
     g_err[0] = 0;
     if (int rc = check_pool(pool)) return rc;
-    if (flags & ~(RAGC_ATTN_APPEND_FUSED | RAGC_ATTN_NO_SPLIT)) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
+    if (flags & ~kAttnFlags) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
     if (q_heads <= 0 || q_heads % pool->kv_heads != 0)
         return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
         return fail(RAGC_ERR_SHAPE, "softmax_scale must be positive and finite");
+    const bool validate = (flags & RAGC_ATTN_VALIDATE) != 0;
     BatchInfo info;
-    if (int rc = check_batch(pool, batch, true, &info)) return rc;
+    HostMeta h;
+    if (int rc = check_batch(pool, batch, true, validate, &h, &info)) return rc;
     if (batch->num_reqs == 0 || info.total_new == 0) return RAGC_OK;
     if (!q || !k_new || !v_new || !out) return fail(RAGC_ERR_NULL, "q / k_new / v_new / out is NULL");
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
         return fail(RAGC_ERR_ALIGN, "q / k_new / v_new / out must be 16-byte aligned");
+    if (validate)
+        if (int rc = validate_batch(pool, batch, h, (flags & RAGC_ATTN_APPEND_FUSED) != 0)) return rc;
 
     ragc::AttnLaunch a;
     a.b = make_paged(pool, batch);
@@ -237,8 +345,7 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
         return RAGC_OK;
     }
     Bf16Plan plan;
-    if (int rc = plan_bf16(pool, batch, a.group, flags, &plan)) return rc;
-    const int S = plan.splits;
+    if (int rc = plan_bf16(pool, batch, h, a.group, flags, &plan)) return rc;
     if (plan.workspace > 0) {
         if (!workspace || (int64_t)workspace_bytes < plan.workspace)
             return fail(RAGC_ERR_WORKSPACE, "workspace of %lld bytes needed (ragc_prefill_attn_workspace), %zu given",
@@ -246,30 +353,72 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RAGC_ERR_ALIGN, "workspace must be 256-byte aligned");
         a.partial = workspace;
     }
-    // every copy of an item is a list entry of its own; a launch takes kAttnMaxItems entries
-    const size_t per_launch = (size_t)ragc::kAttnMaxItems / S;
-    for (size_t i = 0; i < plan.items.size(); i += per_launch) {
-        ragc::AttnWorkList wl{}, leads{};
-        wl.splits = leads.splits = S;
-        wl.part_base = leads.part_base = (int32_t)(i * S);
-        const size_t cnt = std::min(per_launch, plan.items.size() - i);
-        for (size_t j = 0; j < cnt; ++j) {
-            for (int c = 0; c < S; ++c) wl.item[wl.n++] = plan.items[i + j].it;
-            leads.item[leads.n++] = plan.items[i + j].it;
-        }
-        hipError_t e = ragc::launch_attn_bf16(a, wl, plan.variant, s);
-        if (e == hipSuccess && S > 1) e = ragc::launch_attn_bf16_merge(a, leads, s);
-        if (e != hipSuccess) return hip_fail(e, "prefill attention launch");
-    }
+    return run_bf16_plan(a, plan, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ragc_version(void) { return 100; }
+
+const char* ragc_last_error(void) { return g_err; }
+
+int64_t ragc_kv_bytes_per_token(int32_t layers, int32_t kv_heads, int32_t head_dim, int32_t dtype) {
+    const int es = esize_of(dtype);
+    if (layers <= 0 || kv_heads <= 0 || head_dim <= 0 || es == 0) return 0;
+    return (int64_t)2 * layers * kv_heads * head_dim * es;
+}
+
+int ragc_debug_set_attn_plan(int32_t variant, int32_t splits) {
+    g_err[0] = 0;
+    if (variant < -1 || variant >= ragc::kAttnVariantCount) return fail(RAGC_ERR_SHAPE, "variant %d unknown", variant);
+    if (splits < 0 || splits > ragc::kAttnMaxSplits) return fail(RAGC_ERR_SHAPE, "splits %d outside [0, %d]", splits, ragc::kAttnMaxSplits);
+    g_force_variant.store(variant, std::memory_order_relaxed);
+    g_force_splits.store(splits, std::memory_order_relaxed);
     return RAGC_OK;
+}
+
+int ragc_batch_validate(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t writes_new_tokens) {
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    BatchInfo info;
+    HostMeta h;
+    if (int rc = check_batch(pool, batch, true, true, &h, &info)) return rc;
+    if (batch->num_reqs == 0) return RAGC_OK;
+    return validate_batch(pool, batch, h, writes_new_tokens != 0);
+}
+
+int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* batch, int32_t q_heads, uint32_t flags) {
+    g_err[0] = 0;
+    if (int rc = check_pool(pool)) return rc;
+    if (flags & ~kAttnFlags) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
+    if (q_heads <= 0 || q_heads % pool->kv_heads != 0)
+        return fail(RAGC_ERR_SHAPE, "q_heads %d not a multiple of kv_heads %d", q_heads, pool->kv_heads);
+    BatchInfo info;
+    HostMeta h;
+    if (int rc = check_batch(pool, batch, false, false, &h, &info)) return rc;
+    if (pool->dtype != RAGC_DTYPE_BF16 || batch->num_reqs == 0 || info.total_new == 0) return 0;
+    Bf16Plan plan;
+    if (int rc = plan_bf16(pool, batch, h, q_heads / pool->kv_heads, flags, &plan)) return rc;
+    return plan.workspace;
+}
+
+int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+                      const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    return prefill_attn_impl(pool, batch, q, k_new, v_new, out, q_heads, softmax_scale, flags, workspace, workspace_bytes,
+                             stream);
 }
 
 int ragc_kv_append(const ragc_kv_pool* pool, const ragc_batch* batch, const void* k_new, const void* v_new, void* stream) {
     g_err[0] = 0;
     if (int rc = check_pool(pool)) return rc;
     BatchInfo info;
-    if (int rc = check_batch(pool, batch, true, &info)) return rc;
+    HostMeta h;
+    if (int rc = check_batch(pool, batch, true, false, &h, &info)) return rc;
     if (batch->num_reqs == 0 || info.total_new == 0) return RAGC_OK;
+    if (int rc = check_packed(batch, h)) return rc;
     if (!k_new || !v_new) return fail(RAGC_ERR_NULL, "k_new / v_new is NULL");
     if (!aligned16(k_new) || !aligned16(v_new)) return fail(RAGC_ERR_ALIGN, "k_new / v_new must be 16-byte aligned");
     const hipError_t e = ragc::launch_append(make_paged(pool, batch), pool->k, pool->v, k_new, v_new, (int32_t)info.total_new,

@@ -90,8 +90,43 @@ def test_attention_argument_errors(lib):
     assert _attn_code(_pool(), b5) == B.RAGC_ERR_RANGE
     assert "block_table[1] = 64" in B.ragc_last_error()
     hp = np.asarray([1], np.int32)
-    b6 = B.make_batch(1, 4, A, A, A, A, None, hp, hp, None)
-    assert _attn_code(_pool(), b6) == B.RAGC_ERR_NULL
+    b6 = B.make_batch(1, 4, None, None, None, None, None, hp, hp, None)  # no host copy and no device array to read it from
+    with pytest.raises(B.RagcError) as e:
+        B.ragc_prefill_attn_workspace(_pool(), b6, 8)
+    assert e.value.code == B.RAGC_ERR_NULL and "prefix_len" in B.ragc_last_error()
+
+
+def test_append_wants_rows_packed_in_request_order(lib):
+    """The append kernel finds a row's request by searching new_start, so the offsets must be the
+    running sum of new_len; attention takes any offsets.  Both checks happen before any launch."""
+    hp, hn = np.asarray([10, 20, 5], np.int32), np.asarray([5, 0, 7], np.int32)
+    for hs, ok in ((np.asarray([0, 5, 5, 12], np.int32), True), (np.asarray([3, 8, 8, 15], np.int32), True),
+                   (np.asarray([0, 6, 6, 13], np.int32), False), (np.asarray([7, 0, 0, 0], np.int32), False)):
+        b = B.make_batch(3, 4, A, A, A, A, hp, hn, hs, None)
+        if ok:
+            continue  # would launch: covered by the GPU tests
+        with pytest.raises(B.RagcError) as e:
+            B.ragc_kv_append(_pool(), b, A, A)
+        assert e.value.code == B.RAGC_ERR_RANGE and "packed in request order" in B.ragc_last_error()
+
+
+def test_debug_plan_override_changes_the_workspace_and_rejects_bad_values(lib):
+    one, keep = _batch(p=(4096,), n=(16,), stride=300)
+    pool = _pool(num_blocks=512)
+    auto = B.ragc_prefill_attn_workspace(pool, one, 8)
+    try:
+        B.ragc_debug_set_attn_plan(-1, 3)
+        assert B.ragc_prefill_attn_workspace(pool, one, 8) == 3 * 2 * 128 * (128 + 2) * 4
+        B.ragc_debug_set_attn_plan(0, 1)
+        assert B.ragc_prefill_attn_workspace(pool, one, 8) == 0
+        for bad in ((2, 0), (-2, 0), (0, 17), (0, -1)):
+            with pytest.raises(B.RagcError) as e:
+                B.ragc_debug_set_attn_plan(*bad)
+            assert e.value.code == B.RAGC_ERR_SHAPE
+        assert B.ragc_prefill_attn_workspace(pool, one, 8) == 0  # a rejected call leaves the setting alone
+    finally:
+        B.ragc_debug_set_attn_plan(-1, 0)
+    assert B.ragc_prefill_attn_workspace(pool, one, 8) == auto
 
 
 def test_size_limits_and_workspace_errors(lib):

@@ -28,6 +28,16 @@ def H():
     return harness
 
 
+@pytest.fixture
+def force_plan(H):
+    """Override the library's choice of kernel variant / number of key copies for one test."""
+    def set_plan(variant=-1, splits=0):
+        B.ragc_debug_set_attn_plan(-1 if variant is None else variant, 0 if splits is None else splits)
+
+    yield set_plan
+    B.ragc_debug_set_attn_plan(-1, 0)
+
+
 def _bits(t):
     """Integer view of a tensor so NaN poison compares equal to itself."""
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
@@ -78,25 +88,13 @@ def test_config2_full_size_all_rows(H):
     _check_all(H, W.make_config(2), B.RAGC_ATTN_APPEND_FUSED)
 
 
-@pytest.mark.parametrize("index,peaked", [(2, True), (3, False), (3, True), (4, False), (4, True)])
-def test_full_size_configs_sampled_rows(H, index, peaked):
+@pytest.mark.parametrize("index,peaked", [(2, True), (3, False), (3, True), (4, False), (4, True), (5, False), (5, True)])
+def test_full_size_configs_all_rows(H, index, peaked):
+    """Every row of the full-size configurations, plain and with a sharp softmax (Q x 8), in the
+    launch configuration the benchmark times (fused append, the library's own plan)."""
     w = W.make_config(index, peaked=peaked)
-    dw = H.DeviceWorkload(w)
-    out = dw.attn(B.RAGC_ATTN_APPEND_FUSED)
-    torch.cuda.synchronize()
-    got_all = U.out_to_f64(H.to_host(out), w.dtype)
-    assert np.all(np.isfinite(got_all))
-    worst, num, den = 0.0, 0.0, 0.0
-    for r in range(w.num_reqs):
-        rows = U.sample_rows(w, r, 48, seed=index)
-        want = U.oracle_rows(w, r, rows)
-        s0 = int(w.new_start[r])
-        got = np.stack([got_all[s0 + i, h] for i, h in rows])
-        worst = max(worst, float(np.max(np.abs(got - want))))
-        num += float(np.sum((got - want) ** 2))
-        den += float(np.sum(want**2))
-    assert worst <= U.TOL[w.dtype], f"{w.name}: max abs err {worst}"
-    assert (num / den) ** 0.5 <= REL_L2[w.dtype]
+    dw, got, want = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    assert float(np.max(np.abs(want))) > (0.5 if peaked else 0.0)
 
 
 def test_single_key_returns_v_bit_exact(H):
@@ -314,10 +312,10 @@ def test_empty_batches_are_no_ops(H):
 
 
 @pytest.mark.parametrize("variant", [0, 1])
-def test_every_kernel_variant_matches_oracle(H, variant, monkeypatch):
+def test_every_kernel_variant_matches_oracle(H, variant, force_plan):
     """The library picks a kernel variant from the batch shape; force each one
-    (RAGC_ATTN_VARIANT) on a ragged GQA batch and on a long-prefix MHA request."""
-    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
+    (ragc_debug_set_attn_plan) on a ragged GQA batch and on a long-prefix MHA request."""
+    force_plan(variant)
     w = W.make_small("bf16", 8, 2, 128, [(0, 17), (37, 20), (64, 1), (100, 133), (15, 0), (300, 250), (1030, 70)], seed=7001)
     dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
     pk, pv = w.pool_image()
@@ -329,13 +327,12 @@ def test_every_kernel_variant_matches_oracle(H, variant, monkeypatch):
 
 @pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("splits", [2, 3, 7, 16])
-def test_key_split_across_workgroups_matches_oracle(H, variant, splits, monkeypatch):
+def test_key_split_across_workgroups_matches_oracle(H, variant, splits, force_plan):
     """With few work items the library splits each one along its keys over several workgroups and
-    merges their partial results; force the number of copies (RAGC_ATTN_SPLITS) on batches whose
+    merges their partial results; force the number of copies (ragc_debug_set_attn_plan) on batches whose
     items have more, as many and fewer key tiles than copies, rows that see no key of a copy,
     decode steps (one new token), and check the fused append (done by the last copy)."""
-    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
-    monkeypatch.setenv("RAGC_ATTN_SPLITS", str(splits))
+    force_plan(variant, splits)
     w = W.make_small("bf16", 8, 2, 128, [(0, 17), (37, 20), (64, 1), (100, 133), (15, 0), (300, 250), (1030, 70), (2000, 1)], seed=7101)
     dw = H.DeviceWorkload(w)
     assert B.ragc_prefill_attn_workspace(dw.pool, dw.batch, w.q_heads, B.RAGC_ATTN_APPEND_FUSED) > 0
@@ -351,7 +348,7 @@ def test_key_split_across_workgroups_matches_oracle(H, variant, splits, monkeypa
     _check_all(H, W.make_small("bf16", 4, 4, 64, [(700, 100), (5, 260), (900, 1)], seed=7102, q_gain=6.0))
     # the same result with and without the split, bit for bit in what is unique: the appended pool
     _, got_split, want = _check_all(H, W.make_small("bf16", 32, 8, 128, [(4096, 1)] * 3, seed=7103))
-    monkeypatch.setenv("RAGC_ATTN_SPLITS", "1")
+    force_plan(variant, 1)
     _, got_one, _ = _check_all(H, W.make_small("bf16", 32, 8, 128, [(4096, 1)] * 3, seed=7103))
     assert np.max(np.abs(got_split - got_one)) <= 2e-3
 
@@ -370,21 +367,19 @@ def test_split_is_chosen_for_a_single_request_and_for_decode_steps(H):
 
 
 @pytest.mark.parametrize("variant,splits", [(0, 1), (1, 1), (0, 3), (1, None)])
-def test_long_prefix_walks_several_block_id_windows(H, variant, splits, monkeypatch):
+def test_long_prefix_walks_several_block_id_windows(H, variant, splits, force_plan):
     """20,000 cached tokens: 313 key tiles, so a wave refills its 64-entry window of block ids
     several times (and, split along the keys, starts in the middle of the table)."""
-    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(variant))
-    if splits is not None:
-        monkeypatch.setenv("RAGC_ATTN_SPLITS", str(splits))
+    force_plan(variant, splits)
     w = W.make_small("bf16", 8, 2, 128, [(20000, 40), (9000, 1)], seed=7301, q_gain=3.0)
     _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
 
 
-@pytest.mark.parametrize("seed", range(12))
-def test_randomised_shapes_match_oracle(H, seed, monkeypatch):
+def _random_case(seed, gains):
     """Random head counts (group sizes 1-8, also odd ones), head dims, batch sizes and lengths
-    (empty requests, empty prefixes, single tokens, lengths around tile edges), random kernel
-    variant and number of key copies; output against the oracle and appended pool byte for byte."""
+    (empty requests, empty prefixes, single tokens, lengths around tile edges), a random kernel
+    variant and number of key copies.  Values ~ N(0,1): with a sharp softmax |O| reaches max |V|,
+    above 4, where half a unit of the bf16 output grid is 2^-6 of the 2e-2 budget's 1.28 units."""
     import random
 
     rng = random.Random(9000 + seed)
@@ -399,17 +394,40 @@ def test_randomised_shapes_match_oracle(H, seed, monkeypatch):
         lens.append((p, n))
     if all(n == 0 for _, n in lens):
         lens.append((rng.randrange(0, 300), 5))
-    monkeypatch.setenv("RAGC_ATTN_VARIANT", str(rng.randrange(2)))
-    if rng.random() < 0.6:
-        monkeypatch.setenv("RAGC_ATTN_SPLITS", str(rng.choice([1, 2, 3, 4, 5, 8, 16])))
-    # values ~ N(0,1) * 0.5 as in the benchmark configurations: with a sharp softmax |O| reaches max |V|, and
-    # above 2 the bf16 output grid itself is 2^-6 wide or more, which leaves the 2e-2 gate no room
-    w = W.make_small("bf16", hkv * group, hkv, d, lens, seed=9100 + seed, sigma=0.5, q_gain=rng.choice([1.0, 2.0, 8.0]))
-    dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+    variant = rng.randrange(2)
+    splits = rng.choice([1, 2, 3, 4, 5, 8, 16]) if rng.random() < 0.6 else 0
+    w = W.make_small("bf16", hkv * group, hkv, d, lens, seed=9100 + seed, q_gain=rng.choice(gains))
+    return w, variant, splits
+
+
+def _check_with_append(H, w):
+    dw, got, want = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
     pk, pv = w.pool_image()
     OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
     assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
     assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
+    return got, want
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_randomised_shapes_match_oracle(H, seed, force_plan):
+    """Unit-variance values and sharp softmaxes (q gain up to 8): output against the oracle at
+    2e-2 everywhere, and the appended pool byte for byte."""
+    w, variant, splits = _random_case(seed, [1.0, 4.0, 8.0])
+    force_plan(variant, splits)
+    _check_with_append(H, w)
+
+
+def test_large_outputs_sharp_softmax_unit_variance(H, force_plan):
+    """The case that once missed the gate by one output ulp (|O| = 4.1, error 0.0205) when the
+    row sum was taken over unrounded probabilities while P.V used rounded ones: seed 11 of the
+    recipe above with its original gains.  |O| stays below 8, so the flat 2e-2 bound applies."""
+    w, variant, splits = _random_case(11, [1.0, 1.0, 4.0])
+    force_plan(variant, splits)
+    got, want = _check_with_append(H, w)
+    assert np.max(np.abs(want)) > 2.5  # the regime is really reached
+    big = np.abs(want) >= 2.0
+    assert np.max(np.abs(got - want)[big]) <= 2e-2
 
 
 def test_many_work_items_take_several_launches(H):
