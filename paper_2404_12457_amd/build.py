@@ -1,4 +1,5 @@
-"""Build libragc.so (the C-ABI library) for gfx950 with hipcc, in-tree.
+"""Build libragc.so (the C-ABI library) and libragc_calib.so (the benchmark's calibration
+kernels) for gfx950 with hipcc, in-tree.
 
     python -m paper_2404_12457_amd.build
 
@@ -16,6 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libragc.so")
+CALIB_LIB = os.path.join(HERE, "libragc_calib.so")
 SOURCES = ["ragc_api.cpp", "ragc_ctl.cpp", "kv_ops.hip", "attn_f32.hip", "attn_bf16.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
@@ -41,11 +43,11 @@ def _compile(src: str, extra) -> str:
 def build(extra_flags=(), verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    subprocess.run(cmd, check=True)
+        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES + ["calib.hip"]))
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs[:-1]], check=True)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", CALIB_LIB, objs[-1]], check=True)
     if verbose:
-        print("built", LIB)
+        print("built", LIB, "and", CALIB_LIB)
     return LIB
 
 
