@@ -340,6 +340,8 @@ def main():
                     help="pool copies rotated between steps (1 = every step re-reads the same, cache-warm buffers)")
     ap.add_argument("--separate-pools", action="store_true",
                     help="give every rotated copy a pool of its own instead of disjoint blocks of one pool")
+    ap.add_argument("--force-variant", type=int, default=-1, help="debug: kernel variant for every bf16 attention call (-1 = library's choice)")
+    ap.add_argument("--force-splits", type=int, default=0, help="debug: copies of every work item along the keys (0 = library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 512 MiB device copy three times (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -355,6 +357,8 @@ def main():
     from paper_2404_12457_amd import workload as W
 
     B.load()  # fails loudly if libragc.so is missing
+    if args.force_variant >= 0 or args.force_splits > 0:
+        B.ragc_debug_set_attn_plan(args.force_variant, args.force_splits)
     if args.calibrate_copy:
         src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

@@ -23,14 +23,23 @@ constexpr bf16x2 kOnes2 = {(__bf16)1.0f, (__bf16)1.0f};
 // land at lds_addr + 16*i.  Issued as inline assembly on purpose: the compiler's own
 // bookkeeping for this instruction drains every outstanding load before the next LDS read,
 // which would serialise the ring; the waits are placed by hand (wait_vmcnt + block_barrier).
+// The s_nop is required: the LDS address travels in M0, and a scalar write of M0 needs one wait
+// state before an LDS-DMA instruction reads it (inside inline assembly nobody inserts it for us;
+// without it the copy can land at the previous instruction's LDS address).
 __device__ __forceinline__ void dma_16B_per_lane(const void* gptr, uint32_t lds_addr) {
     lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);  // wave-uniform by construction; make the register class explicit
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 // same with a wave-uniform base address and a 32-bit per-lane byte offset
 __device__ __forceinline__ void dma_16B_per_lane(uint64_t sbase, uint32_t lane_off, uint32_t lds_addr) {
     lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase) : "memory", "m0");
+    // a scalar register pair whatever the compiler knows or does not know about the value
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)sbase), hi = __builtin_amdgcn_readfirstlane((uint32_t)(sbase >> 32));
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    sbase = ((uint64_t)hi << 32) | lo;
+    // No "memory" clobber: the slot this copy writes is not read before the next barrier (which has
+    // one), and without it the compiler may move the LDS reads of the current tile across the copy.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(sbase) : "m0");
 }
 __device__ __forceinline__ uint64_t uniform_u64(const void* p) {
     const uint64_t v = reinterpret_cast<uint64_t>(p);
