@@ -78,7 +78,7 @@
  *     range-checked) and flags (copy mechanism).
  *   - the fused-append flag is spelled RAGC_ATTN_APPEND_FUSED; RAGC_ATTN_NO_SPLIT is new.
  *   - more exports: ragc_last_error, ragc_kv_bytes_per_token, ragc_prefill_attn_workspace,
- *     ragc_batch_validate, ragc_debug_set_attn_plan.
+ *     ragc_batch_validate, ragc_debug_set_attn_plan, ragc_prefill_attn_static.
  *   - host copies of the lengths are optional but their absence costs a synchronous
  *     read-back per call (the launch is sized on the host).
  */
@@ -220,6 +220,27 @@ int64_t ragc_prefill_attn_workspace(const ragc_kv_pool* pool, const ragc_batch* 
 int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ragc_prefill_attn for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments minus the workspace, same kernels, same results; the
+ * partial results of key-split work items go to an array that is part of the library's
+ * device image (17,039,360 bytes, held by every GPU the library runs on until the process
+ * ends) instead.  The call allocates nothing and does not synchronise:
+ *   - h_prefix_len, h_new_len and h_new_start are required (RAGC_ERR_NULL otherwise) and
+ *     RAGC_ATTN_VALIDATE is rejected, because both would read device memory back;
+ *   - a batch whose partial results exceed the array returns RAGC_ERR_WORKSPACE and
+ *     launches nothing (cannot happen with the library's own choice of split on a GPU of
+ *     up to 256 compute units; it can under ragc_debug_set_attn_plan);
+ *   - every call on one GPU shares that GPU's array: calls that may overlap (different
+ *     streams, or different threads on one device) race -- serialise them or use
+ *     ragc_prefill_attn with workspaces of their own.  Nothing in it needs clearing
+ *     between calls: every value that is read was written by the same call.
+ *   The first call on a device looks the array's address up (and may load the device
+ *   image); make that call before starting a graph capture. */
+int ragc_prefill_attn_static(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
+                             void* stream);
 
 /* Write the fresh K/V of every request into its paged slots (Sec. 4: the tensors
  * of the accessed documents are cached after the first token): row

@@ -24,7 +24,7 @@ RAGC_SWAP_AUTO, RAGC_SWAP_MEMCPY, RAGC_SWAP_KERNEL = 0, 1, 2
 RAGC_SWAP_TO_DEVICE, RAGC_SWAP_TO_HOST = 0, 1
 
 EXPORTS = ["ragc_version", "ragc_last_error", "ragc_kv_bytes_per_token", "ragc_prefill_attn_workspace",
-           "ragc_prefill_attn", "ragc_kv_append", "ragc_kv_swap", "ragc_kv_gather",
+           "ragc_prefill_attn", "ragc_prefill_attn_static", "ragc_kv_append", "ragc_kv_swap", "ragc_kv_gather",
            "ragc_batch_validate", "ragc_debug_set_attn_plan"]
 
 
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
         lib.ragc_prefill_attn_workspace.argtypes = [P, P, I32, U32]
         lib.ragc_prefill_attn.restype = ctypes.c_int
         lib.ragc_prefill_attn.argtypes = [P, P, P, P, P, P, I32, ctypes.c_float, U32, P, ctypes.c_size_t, P]
+        lib.ragc_prefill_attn_static.restype = ctypes.c_int
+        lib.ragc_prefill_attn_static.argtypes = [P, P, P, P, P, P, I32, ctypes.c_float, U32, P]
         lib.ragc_batch_validate.restype = ctypes.c_int
         lib.ragc_batch_validate.argtypes = [P, P, I32]
         lib.ragc_debug_set_attn_plan.restype = ctypes.c_int
@@ -134,6 +136,12 @@ def ragc_prefill_attn(pool, batch, q, k_new, v_new, out, q_heads: int, softmax_s
                       workspace=None, workspace_bytes: int = 0, stream: int = 0) -> int:
     return _check(load().ragc_prefill_attn(_ref(pool), _ref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), q_heads,
                                            softmax_scale, flags, _ptr(workspace), workspace_bytes, stream or None))
+
+
+def ragc_prefill_attn_static(pool, batch, q, k_new, v_new, out, q_heads: int, softmax_scale: float, flags: int = 0,
+                             stream: int = 0) -> int:
+    return _check(load().ragc_prefill_attn_static(_ref(pool), _ref(batch), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                  q_heads, softmax_scale, flags, stream or None))
 
 
 def ragc_batch_validate(pool, batch, writes_new_tokens: bool = True) -> int:

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "ragc_internal.h"
@@ -301,9 +302,37 @@ int run_bf16_plan(ragc::AttnLaunch& a, const Bf16Plan& plan, hipStream_t s) {
     return RAGC_OK;
 }
 
+// ---- partial results of key-split work items for callers that cannot allocate --------------
+// One array per GPU (every device that loads the library holds its own copy until the process
+// ends).  Host code must never pass the array's name to a kernel: that name is a host-side
+// stand-in; the device address comes from hipGetSymbolAddress, once per device.
+constexpr int64_t kStaticScratchBytes = 256 * 128 * (128 + 2) * 4;  // 256 partial results at head_dim 128: 17,039,360 bytes
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(RAGC_ERR_RANGE, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // address of THIS device's copy
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return fail(RAGC_ERR_ALIGN, "static scratch is not 256-byte aligned");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RAGC_OK;
+}
+
 int prefill_attn_impl(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
                       const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
-                      void* workspace, size_t workspace_bytes, void* stream) {
+                      void* workspace, size_t workspace_bytes, bool use_static_scratch, void* stream) {
     g_err[0] = 0;
     if (int rc = check_pool(pool)) return rc;
     if (flags & ~kAttnFlags) return fail(RAGC_ERR_SHAPE, "unknown flags 0x%x", flags);
@@ -312,6 +341,12 @@ int prefill_attn_impl(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     if (!(softmax_scale > 0.f) || !std::isfinite(softmax_scale))
         return fail(RAGC_ERR_SHAPE, "softmax_scale must be positive and finite");
     const bool validate = (flags & RAGC_ATTN_VALIDATE) != 0;
+    if (use_static_scratch) {
+        // nothing in this mode may allocate or synchronise: no read-backs
+        if (validate) return fail(RAGC_ERR_SHAPE, "RAGC_ATTN_VALIDATE reads device arrays back; not available in ragc_prefill_attn_static");
+        if (batch && batch->num_reqs > 0 && (!batch->h_prefix_len || !batch->h_new_len || !batch->h_new_start))
+            return fail(RAGC_ERR_NULL, "ragc_prefill_attn_static needs h_prefix_len, h_new_len and h_new_start");
+    }
     BatchInfo info;
     HostMeta h;
     if (int rc = check_batch(pool, batch, true, validate, &h, &info)) return rc;
@@ -347,11 +382,18 @@ int prefill_attn_impl(const ragc_kv_pool* pool, const ragc_batch* batch, const v
     Bf16Plan plan;
     if (int rc = plan_bf16(pool, batch, h, a.group, flags, &plan)) return rc;
     if (plan.workspace > 0) {
-        if (!workspace || (int64_t)workspace_bytes < plan.workspace)
-            return fail(RAGC_ERR_WORKSPACE, "workspace of %lld bytes needed (ragc_prefill_attn_workspace), %zu given",
-                        (long long)plan.workspace, workspace_bytes);
-        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RAGC_ERR_ALIGN, "workspace must be 256-byte aligned");
-        a.partial = workspace;
+        if (use_static_scratch) {
+            if (plan.workspace > kStaticScratchBytes)
+                return fail(RAGC_ERR_WORKSPACE, "this batch needs %lld bytes for its partial results; the static scratch holds %lld",
+                            (long long)plan.workspace, (long long)kStaticScratchBytes);
+            if (int rc = static_scratch(&a.partial)) return rc;
+        } else {
+            if (!workspace || (int64_t)workspace_bytes < plan.workspace)
+                return fail(RAGC_ERR_WORKSPACE, "workspace of %lld bytes needed (ragc_prefill_attn_workspace), %zu given",
+                            (long long)plan.workspace, workspace_bytes);
+            if (reinterpret_cast<uintptr_t>(workspace) & 255u) return fail(RAGC_ERR_ALIGN, "workspace must be 256-byte aligned");
+            a.partial = workspace;
+        }
     }
     return run_bf16_plan(a, plan, s);
 }
@@ -408,7 +450,13 @@ int ragc_prefill_attn(const ragc_kv_pool* pool, const ragc_batch* batch, const v
                       const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
                       void* workspace, size_t workspace_bytes, void* stream) {
     return prefill_attn_impl(pool, batch, q, k_new, v_new, out, q_heads, softmax_scale, flags, workspace, workspace_bytes,
-                             stream);
+                             false, stream);
+}
+
+int ragc_prefill_attn_static(const ragc_kv_pool* pool, const ragc_batch* batch, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t q_heads, float softmax_scale, uint32_t flags,
+                             void* stream) {
+    return prefill_attn_impl(pool, batch, q, k_new, v_new, out, q_heads, softmax_scale, flags, nullptr, 0, true, stream);
 }
 
 int ragc_kv_append(const ragc_kv_pool* pool, const ragc_batch* batch, const void* k_new, const void* v_new, void* stream) {

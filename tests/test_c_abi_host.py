@@ -94,6 +94,12 @@ def test_attention_argument_errors(lib):
     with pytest.raises(B.RagcError) as e:
         B.ragc_prefill_attn_workspace(_pool(), b6, 8)
     assert e.value.code == B.RAGC_ERR_NULL and "prefix_len" in B.ragc_last_error()
+    with pytest.raises(B.RagcError) as e:  # the entry point that may not read anything back wants all three host copies
+        B.ragc_prefill_attn_static(_pool(), B.make_batch(1, 4, A, A, A, A, None, hp, hp, None), A, A, A, A, 8, 0.1)
+    assert e.value.code == B.RAGC_ERR_NULL
+    with pytest.raises(B.RagcError) as e:
+        B.ragc_prefill_attn_static(_pool(), b, A, A, A, A, 8, 0.1, B.RAGC_ATTN_VALIDATE)
+    assert e.value.code == B.RAGC_ERR_SHAPE
 
 
 def test_append_wants_rows_packed_in_request_order(lib):
