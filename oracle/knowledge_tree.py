@@ -25,6 +25,12 @@ What the paper leaves open, and the reading taken here (the C++ side documents t
   the host tier cannot make room for a first copy, the node and everything below it leave the
   cache.  A first copy that a request asked for is struck from its list again when, later in
   the same request, the host tier drops that node (its slot may already be promised to another).
+* Requests in flight together.  A node created by a request that has not ended yet has its
+  blocks reserved but its K/V not written; it cannot serve another request as cached prefix
+  (the paper batches several requests per prefill iteration, Sec. 7, and says nothing about
+  this).  Prefix matching therefore stops at such a node; the second request computes that
+  document and everything after it for itself in blocks of its own, adds nothing to the tree
+  below that point, and counts as one more computation of the nodes that exist (numComputed).
 * Block ids come from a LIFO free list that starts as 0, 1, 2, ... (so results are
   reproducible); this order is part of what the C++ side is compared on.
 * Outside the profiled grid T is extrapolated linearly from the two nearest grid lines of
@@ -78,6 +84,7 @@ class Node:
     AvgCost: float = 0.0
     Priority: List[float] = field(default_factory=lambda: [0.0, 0.0])  # per tier
     pins: int = 0
+    computed: bool = False  # its K/V has been written: set when the request that created the node ends
 
     @property
     def tok_end(self) -> int:
@@ -113,6 +120,7 @@ class KnowledgeTree:
         self.Clock = [0.0, 0.0]
         self.root = Node(0, -1, 0, 0, None)
         self.root.pins = 1  # never a candidate
+        self.root.computed = True
         self.next_ident = 1
         self.next_request = 1
         self.requests: Dict[int, Tuple[List[Node], List[int]]] = {}
@@ -223,24 +231,37 @@ class KnowledgeTree:
         docs_total = sum(doc_lens)
         total = docs_total + question_len
         plan = Plan(self.next_request, 0, 0, 0, [], [], [], [], [])
-        # prefix matching: stop at the first document that is not a child
+        # prefix matching: stop at the first document that is not a child -- or whose node belongs to a
+        # request still in flight: its blocks are reserved but its K/V is not written yet, so it cannot
+        # serve as a cached prefix
         path: List[Node] = []
         cur = self.root
         for d, l in zip(doc_ids, doc_lens):
             nxt = cur.children.get(d)
-            if nxt is None:
+            if nxt is None or not nxt.computed:
                 break
             assert nxt.length == l, "a document id has one length"
             path.append(nxt)
             cur = nxt
         m = len(path)
+        # The next document has a node that is being computed elsewhere: this request computes the
+        # document for itself in blocks of its own and adds nothing to the tree below that point.
+        in_progress: List[Node] = []
+        nxt = cur
+        for d, l in zip(doc_ids[m:], doc_lens[m:]):
+            nxt = nxt.children.get(d)
+            if nxt is None:
+                break
+            assert nxt.length == l, "a document id has one length"
+            in_progress.append(nxt)
+        blocked = bool(in_progress)
         for n in path:
             n.pins += 1
         matched_end = path[-1].tok_end if path else 0
         alpha = matched_end // BLOCK * BLOCK
         beta = total - alpha
         blocks_total = (total + BLOCK - 1) // BLOCK
-        cacheable = docs_total // BLOCK
+        cacheable = alpha // BLOCK if blocked else docs_total // BLOCK
         to_swap_in = [n for n in path if n.where == HOST]
         need = sum(n.n_owned for n in to_swap_in) + (blocks_total - alpha // BLOCK)
         if need > len(self.free_dev) + self._freeable(self.root)[1]:
@@ -258,7 +279,7 @@ class KnowledgeTree:
         # new nodes for the documents that were not matched
         new_nodes: List[Node] = []
         tok = matched_end
-        for d, l in zip(doc_ids[m:], doc_lens[m:]):
+        for d, l in (() if blocked else zip(doc_ids[m:], doc_lens[m:])):
             n = Node(self.next_ident, d, l, tok, cur)
             self.next_ident += 1
             n.dev_blocks = [self.free_dev.pop() for _ in range(n.n_owned)]
@@ -275,12 +296,12 @@ class KnowledgeTree:
         # retrieval updates every document's node
         for n in path:
             self._update_node(n, True, alpha, beta)
-        for n in new_nodes:
+        for n in new_nodes + in_progress:  # the documents this request computes (Algorithm 1: is_cached false)
             self._update_node(n, False, alpha, beta)
         self.docs_requested += len(doc_ids)
         self.docs_hit += m
         plan.matched_docs, plan.alpha, plan.beta = m, alpha, beta
-        self.requests[plan.request_id] = (path + new_nodes, private)
+        self.requests[plan.request_id] = (path + new_nodes, private, new_nodes)
         self.next_request += 1
         return plan
 
@@ -289,16 +310,18 @@ class KnowledgeTree:
         cur, matched_end = self.root, 0
         for d in doc_ids:
             cur = cur.children.get(d)
-            if cur is None:
+            if cur is None or not cur.computed:
                 break
             matched_end = cur.tok_end
         alpha = matched_end // BLOCK * BLOCK
         return alpha, sum(doc_lens) + question_len - alpha
 
     def end(self, request_id: int) -> None:
-        nodes, private = self.requests.pop(request_id)
+        nodes, private, created = self.requests.pop(request_id)
         for n in nodes:
             n.pins -= 1
+        for n in created:
+            n.computed = True  # the request has run: the K/V of its new documents is in their blocks
         self.free_dev.extend(private)
 
     def reset_frequencies(self) -> None:
@@ -334,7 +357,8 @@ class KnowledgeTree:
                 assert len(n.host_slots) == n.n_owned
                 used_host += n.host_slots
             assert n.tok_begin == (0 if n.parent is self.root else n.parent.tok_end)
-        for _, private in self.requests.values():
+            assert n.parent is self.root or n.parent.computed or not n.computed  # K/V of a path is written parent first
+        for _, private, _created in self.requests.values():
             used_dev += private
         assert len(set(used_dev)) == len(used_dev) and not set(used_dev) & set(self.free_dev)
         assert len(set(used_host)) == len(used_host) and not set(used_host) & set(self.free_host)

@@ -160,6 +160,51 @@ def test_nodes_of_requests_in_flight_are_not_evicted():
     assert t.begin([2], [64], 0).evicted_gpu == [t.find([1]).ident]
 
 
+def test_a_document_still_being_computed_is_not_a_cached_prefix_for_a_second_request():
+    """Two requests in flight that share a NEW document: the first one's node has its blocks reserved but
+    nothing written, so the second must not attend over them.  It computes the document for itself in
+    blocks of its own, the node counts two computations, and once the first request has ended a third
+    request finds the document cached.  Costs by hand: T = 2*beta, so a request that computes b tokens
+    charges 2*b / b = 2 per token each time."""
+    t = _tree(64, 64, lambda a, b: 2.0 * b)
+    free0 = len(t.free_dev)
+    a = t.begin([7, 8], [40, 24], 8)          # creates nodes [7] and [7, 8]: 72 tokens, 4 owned + 1 private block
+    assert (a.matched_docs, a.alpha, a.beta) == (0, 0, 72)
+    assert not t.find([7]).computed and t.peek([7], [40], 8) == (0, 48)
+    b = t.begin([7, 9], [40, 16], 8)          # [7] exists but is in flight: nothing is cached for b
+    assert (b.matched_docs, b.alpha, b.beta) == (0, 0, 64)
+    assert not set(a.block_table) & set(b.block_table) and len(b.block_table) == 4
+    assert t.find([7, 9]) is None             # b adds nothing below the node it had to wait for
+    n7 = t.find([7])
+    assert (n7.Frequency, n7.numComputed, n7.pins) == (2, 2, 1) and n7.AvgCost == pytest.approx(2.0)
+    assert t.find([7, 8]).numComputed == 1    # b does not go through [7, 8]
+    t.check_invariants()
+    t.end(b.request_id)
+    assert len(t.free_dev) == free0 - 5       # all of b's blocks are back; a still holds its five
+    assert not t.find([7]).computed
+    t.end(a.request_id)
+    assert t.find([7]).computed and t.find([7, 8]).computed
+    c = t.begin([7, 9], [40, 16], 8)          # now [7] serves as prefix: alpha = 32 (whole blocks of 40 tokens)
+    assert (c.matched_docs, c.alpha, c.beta) == (1, 32, 32)
+    assert c.block_table[:2] == a.block_table[:2]
+    assert t.find([7]).numComputed == 2 and t.find([7]).Frequency == 3
+    assert t.find([7, 9]).numComputed == 1 and not t.find([7, 9]).computed
+    t.check_invariants()
+
+
+def test_a_chain_in_flight_blocks_every_document_below_it_and_charges_each_node_once():
+    t = _tree(64, 64, lambda a, b: 1.0 * b)
+    a = t.begin([1, 2, 3], [16, 16, 16], 4)
+    b = t.begin([1, 2, 4], [16, 16, 16], 4)   # [1] and [1, 2] are in flight, [1, 2, 4] does not exist
+    assert (b.matched_docs, b.alpha) == (0, 0) and t.find([1, 2, 4]) is None
+    assert [t.find(p).numComputed for p in ([1], [1, 2], [1, 2, 3])] == [2, 2, 1]
+    t.end(a.request_id)
+    t.end(b.request_id)
+    c = t.begin([1, 2, 4], [16, 16, 16], 4)
+    assert (c.matched_docs, c.alpha, c.beta) == (2, 32, 20)
+    t.check_invariants()
+
+
 def test_cheaper_and_rarer_documents_go_first():
     f = lambda a, b: 1.0 * b + 0.01 * a * b  # per-token cost grows with the cached prefix in front
     t = _tree(10, 64, f)
