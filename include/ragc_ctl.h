@@ -80,7 +80,14 @@ typedef struct ragc_plan {
  * for all alpha + beta tokens and updates frequency, cost and priority of every document of the
  * request (Algorithm 1, UPDATE_NODE_IN_GPU with the request's alpha and beta).  The nodes of the
  * request stay in GPU memory until ragc_tree_end.  RAGC_ERR_RANGE if the request cannot fit even
- * after evicting everything that is not in use: then nothing has changed. */
+ * after evicting everything that is not in use: then nothing has changed.
+ * Requests in flight together (the paper batches several per prefill iteration, Sec. 7): a node
+ * created by a request that has not ended yet has its blocks reserved but its K/V not written, so
+ * it is not a cached prefix for anyone else.  Matching stops at such a node; this request then
+ * computes that document and everything after it in blocks of its own (they return to the free
+ * list at ragc_tree_end), gives none of them a node, and counts as one more computation in the
+ * statistics of the nodes that exist.  Plans of requests in flight together therefore never share
+ * a block that one of them writes, and may be launched in one batch or in any order. */
 int ragc_tree_begin(ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_lens, int32_t n_docs,
                     int32_t question_len, ragc_plan* plan);
 
@@ -94,8 +101,11 @@ typedef struct ragc_plan_buffers {
 } ragc_plan_buffers;
 int ragc_tree_plan_read(const ragc_tree* tree, int64_t request_id, const ragc_plan_buffers* out);
 
-/* The request is done (its K/V has been appended): its nodes may be evicted again and the
- * blocks that no node owns (tail of the last document, question) return to the free list. */
+/* The request is done (its K/V has been appended): the nodes it created become usable as cached
+ * prefix, its nodes may be evicted again and the blocks that no node owns (tail of the last
+ * document, question, documents it computed next to a request in flight) return to the free
+ * list.  Call it only after the attention call that appends the request's K/V has been enqueued
+ * on the stream every later reader uses (or has completed). */
 int ragc_tree_end(ragc_tree* tree, int64_t request_id);
 
 typedef struct ragc_tree_stats {
@@ -114,7 +124,7 @@ typedef struct ragc_node_info {
     int32_t length;      /* tokens */
     int32_t n_owned;     /* blocks */
     int32_t pins;        /* requests in flight that use it */
-    int32_t reserved;
+    int32_t computed;    /* 1 once the request that created the node has ended (its K/V is written) */
     int64_t frequency, num_computed;
     double avg_cost, priority_gpu, priority_host;
 } ragc_node_info;

@@ -76,6 +76,7 @@ struct Node {
     double total_cost = 0.0, avg_cost = 0.0;
     double priority[2] = {0.0, 0.0};
     int pins = 0;
+    bool computed = false;  // its K/V has been written: set when the request that created the node ends
     int gpu_children = 0;
     bool listed[2] = {false, false};  // member of the candidate set of the tier
     double listed_key[2] = {0.0, 0.0};
@@ -86,6 +87,7 @@ struct Node {
 
 struct Request {
     std::vector<Node*> nodes;       // matched and new, in path order (all pinned)
+    std::vector<Node*> created;     // the new ones: computed once this request has ended
     std::vector<int32_t> unowned;   // blocks no node owns
     std::vector<int32_t> table, out_dev, out_slot, in_dev, in_slot;
     std::vector<int64_t> evicted_gpu, evicted_host;
@@ -292,6 +294,7 @@ ragc_tree* ragc_tree_create(int32_t gpu_blocks, int32_t host_slots, const ragc_c
     for (int32_t b = gpu_blocks - 1; b >= 0; --b) t->free_dev.push_back(b);   // back() is 0, then 1, ...
     for (int32_t s = host_slots - 1; s >= 0; --s) t->free_host.push_back(s);
     t->root.pins = 1;
+    t->root.computed = true;
     return t;
 }
 
@@ -315,26 +318,43 @@ int ragc_tree_begin(ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_
     // prefix matching along the path of documents (O(height))
     std::vector<Node*> path;
     Node* cur = &tree->root;
+    // A node whose request is still in flight has its blocks reserved but its K/V not written: it
+    // cannot serve as a cached prefix, so matching stops there as well.
     for (int32_t i = 0; i < n_docs; ++i) {
         const auto it = cur->children.find(doc_ids[i]);
-        if (it == cur->children.end()) break;
+        if (it == cur->children.end() || !it->second->computed) break;
         if (it->second->length != doc_lens[i])
             return set_error(RAGC_ERR_SHAPE, "document id %lld comes with %d tokens, cached with %d", (long long)doc_ids[i], doc_lens[i], it->second->length);
         path.push_back(it->second);
         cur = it->second;
     }
     const int32_t m = (int32_t)path.size();
+    // The next documents have nodes that are being computed elsewhere: this request computes them
+    // for itself in blocks of its own and adds nothing to the tree below that point.
+    std::vector<Node*> in_progress;
+    {
+        const Node* nxt = cur;
+        for (int32_t i = m; i < n_docs; ++i) {
+            const auto it = nxt->children.find(doc_ids[i]);
+            if (it == nxt->children.end()) break;
+            if (it->second->length != doc_lens[i])
+                return set_error(RAGC_ERR_SHAPE, "document id %lld comes with %d tokens, cached with %d", (long long)doc_ids[i], doc_lens[i], it->second->length);
+            in_progress.push_back(it->second);
+            nxt = it->second;
+        }
+    }
+    const bool blocked = !in_progress.empty();
     for (Node* n : path) tree->pin(n, +1);
     const int64_t matched_end = path.empty() ? 0 : path.back()->tok_end();
     const int32_t alpha = (int32_t)(matched_end / kBlk * kBlk);
     const int32_t beta = (int32_t)(total - alpha);
     const int64_t blocks_total = (total + kBlk - 1) / kBlk;
-    const int64_t cacheable = docs_total / kBlk;
+    const int64_t cacheable = blocked ? alpha / kBlk : docs_total / kBlk;
     int64_t need = blocks_total - alpha / kBlk;
     for (Node* n : path)
         if (n->tier == kHost) need += n->n_owned();
     const int64_t have = (int64_t)tree->free_dev.size();
-    if (need > have + tree->freeable(&tree->root).second) {
+    if (need > have && need > have + tree->freeable(&tree->root).second) {  // the walk over the tree only when room is short
         for (Node* n : path) tree->pin(n, -1);
         return set_error(RAGC_ERR_RANGE, "request needs %lld blocks: %lld free, the rest is in use", (long long)need, (long long)have);
     }
@@ -358,7 +378,7 @@ int ragc_tree_begin(ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_
     // a node for every document that was not matched
     rq.nodes = path;
     int64_t tok = matched_end;
-    for (int32_t i = m; i < n_docs; ++i) {
+    for (int32_t i = m; i < (blocked ? m : n_docs); ++i) {
         Node* n = new Node();
         n->id = tree->next_id++;
         n->doc = doc_ids[i];
@@ -375,6 +395,7 @@ int ragc_tree_begin(ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_
         ++tree->n_nodes;
         ++tree->n_nodes_gpu;
         rq.nodes.push_back(n);
+        rq.created.push_back(n);
         cur = n;
         tok += n->length;
     }
@@ -383,7 +404,8 @@ int ragc_tree_begin(ragc_tree* tree, const int64_t* doc_ids, const int32_t* doc_
     rq.table.insert(rq.table.end(), rq.unowned.begin(), rq.unowned.end());
 
     // retrieval updates every document's node
-    for (int32_t i = 0; i < n_docs; ++i) tree->update_node(rq.nodes[i], i < m, alpha, beta);
+    for (size_t i = 0; i < rq.nodes.size(); ++i) tree->update_node(rq.nodes[i], (int32_t)i < m, alpha, beta);
+    for (Node* n : in_progress) tree->update_node(n, false, alpha, beta);  // computed once more, by this request
     tree->docs_requested += n_docs;
     tree->docs_hit += m;
 
@@ -427,6 +449,7 @@ int ragc_tree_end(ragc_tree* tree, int64_t request_id) {
     const auto it = tree->requests.find(request_id);
     if (it == tree->requests.end()) return set_error(RAGC_ERR_RANGE, "request %lld is not in flight", (long long)request_id);
     for (Node* n : it->second.nodes) tree->pin(n, -1);
+    for (Node* n : it->second.created) n->computed = true;  // the request has run: the K/V of its new documents is in their blocks
     tree->free_dev.insert(tree->free_dev.end(), it->second.unowned.begin(), it->second.unowned.end());
     tree->requests.erase(it);
     return 0;
@@ -463,7 +486,7 @@ int ragc_tree_find(const ragc_tree* tree, const int64_t* doc_path, int32_t n, ra
     out->length = cur->length;
     out->n_owned = cur->n_owned();
     out->pins = cur->pins;
-    out->reserved = 0;
+    out->computed = cur->computed ? 1 : 0;
     out->frequency = cur->frequency;
     out->num_computed = cur->num_computed;
     out->avg_cost = cur->avg_cost;
@@ -480,7 +503,7 @@ static void peek_lengths(const ragc_tree* tree, const int64_t* doc_ids, const in
     for (int32_t i = 0; i < n_docs; ++i) total += doc_lens[i];
     for (int32_t i = 0; i < n_docs; ++i) {
         const auto it = cur->children.find(doc_ids[i]);
-        if (it == cur->children.end()) break;
+        if (it == cur->children.end() || !it->second->computed) break;
         cur = it->second;
         matched_end = cur->tok_end();
     }

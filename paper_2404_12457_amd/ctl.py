@@ -10,7 +10,12 @@ from typing import Sequence
 
 import numpy as np
 
+import os
+
 from . import binding as B
+
+# T(alpha, beta) measured with ragc_prefill_attn on one MI355X (see CostGrid.save / bench.py --write-cost-grid)
+MEASURED_GRID = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data", "cost_grid_mi355x_llama2_7b.json")
 
 EXPORTS = ["ragc_cost_interp", "ragc_tree_create", "ragc_tree_destroy", "ragc_tree_begin", "ragc_tree_plan_read",
            "ragc_tree_end", "ragc_tree_get_stats", "ragc_tree_find", "ragc_tree_reset_frequencies", "ragc_tree_peek",
@@ -42,7 +47,7 @@ class ragc_tree_stats(ctypes.Structure):
 
 class ragc_node_info(ctypes.Structure):
     _fields_ = [("id", _I64), ("in_gpu", _I32), ("host_valid", _I32), ("length", _I32), ("n_owned", _I32),
-                ("pins", _I32), ("reserved", _I32), ("frequency", _I64), ("num_computed", _I64), ("avg_cost", _D),
+                ("pins", _I32), ("computed", _I32), ("frequency", _I64), ("num_computed", _I64), ("avg_cost", _D),
                 ("priority_gpu", _D), ("priority_host", _D)]
 
 
@@ -102,6 +107,30 @@ class CostGrid:
         assert self.t.shape == (self.alpha.size, self.beta.size)
         self.c = ragc_cost_grid(self.alpha.size, self.beta.size, self.alpha.ctypes.data, self.beta.ctypes.data,
                                 self.t.ctypes.data)
+        self.meta: dict = {}
+
+    # A profiled table travels as a small JSON file: {"alpha": [...], "beta": [...], "t": [[...]], ...};
+    # any other key (unit, shape, device, noise) is kept in `meta`.  `bench.py --write-cost-grid PATH`
+    # writes one from measurements with the attention kernel; MEASURED_GRID is the copy in this package.
+    def save(self, path: str, **meta) -> None:
+        import json
+
+        doc = dict(self.meta)
+        doc.update(meta)
+        doc.update({"alpha": self.alpha.tolist(), "beta": self.beta.tolist(), "t": self.t.tolist()})
+        with open(path, "w") as f:
+            json.dump(doc, f, indent=1)
+            f.write("\n")
+
+    @classmethod
+    def load(cls, path: str) -> "CostGrid":
+        import json
+
+        with open(path) as f:
+            doc = json.load(f)
+        grid = cls(doc["alpha"], doc["beta"], doc["t"])
+        grid.meta = {k: v for k, v in doc.items() if k not in ("alpha", "beta", "t")}
+        return grid
 
 
 def ragc_cost_interp(grid: CostGrid, alpha: float, beta: float) -> float:

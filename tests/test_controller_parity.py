@@ -3,6 +3,7 @@ every decision is compared (matched documents, alpha, beta, block tables, swap l
 order in both tiers, clocks, statistics, per-node frequency / cost / priorities), and the
 refusals come at the same requests.  CPU only: the controller makes no GPU call."""
 import random
+from collections import Counter
 
 import numpy as np
 import pytest
@@ -37,8 +38,8 @@ def _same_node(no: KT.Node, nc):
         assert nc is None
         return
     assert nc is not None
-    assert (no.ident, no.where == KT.GPU, no.host_valid, no.length, no.n_owned, no.pins, no.Frequency, no.numComputed) == \
-           (nc.id, bool(nc.in_gpu), bool(nc.host_valid), nc.length, nc.n_owned, nc.pins, nc.frequency, nc.num_computed)
+    assert (no.ident, no.where == KT.GPU, no.host_valid, no.length, no.n_owned, no.pins, no.Frequency, no.numComputed, no.computed) == \
+           (nc.id, bool(nc.in_gpu), bool(nc.host_valid), nc.length, nc.n_owned, nc.pins, nc.frequency, nc.num_computed, bool(nc.computed))
     assert nc.avg_cost == pytest.approx(no.AvgCost, rel=1e-13)
     assert nc.priority_gpu == pytest.approx(no.Priority[KT.GPU], rel=1e-13)
     assert nc.priority_host == pytest.approx(no.Priority[KT.HOST], rel=1e-13)
@@ -197,3 +198,115 @@ def test_reordering_example_of_the_paper_through_the_library():
         order.append(i)
     s = tc.stats()
     assert order == [1, 3, 5, 2, 4, 6] and (s.docs_hit, s.docs_requested) == (4, 6)
+
+
+# ---- the measured cost table (T(alpha, beta) of Sec. 5.1, profiled with the attention kernel on an MI355X)
+
+
+def _measured():
+    g = C.CostGrid.load(C.MEASURED_GRID)
+    return g, g.alpha.tolist(), g.beta.tolist(), g.t.tolist()
+
+
+def _zipf_trace(seed, nreq, ndocs):
+    """Top-2 retrieval with skewed popularity, document lengths 256-1024 tokens, 100-token questions."""
+    rng = random.Random(seed)
+    lens = {d: rng.randrange(256, 1025) for d in range(ndocs)}
+    for _ in range(nreq):
+        docs = list(dict.fromkeys(min(int(rng.paretovariate(1.1)) - 1, ndocs - 1) for _ in range(2)))
+        yield docs, [lens[d] for d in docs], 100
+
+
+def test_measured_grid_file_is_well_formed_and_loads():
+    g, alphas, betas, t = _measured()
+    assert g.meta["unit"] == "us" and "MHA" in g.meta["shape"]
+    assert alphas == sorted(set(alphas)) and betas == sorted(set(betas)) and alphas[0] == 0
+    assert np.all(g.t > 0)
+    assert np.all(np.diff(g.t, axis=0) > -0.05 * g.t[1:]) and np.all(np.diff(g.t, axis=1) > -0.05 * g.t[:, 1:])  # grows with both, up to noise
+    assert g.meta["off_grid_max_rel_err"] < 0.05 and g.meta["run_to_run_rel_noise"] < 0.10
+    # on the grid points the library returns the table itself; between them it agrees with the oracle
+    for i in (0, 3, len(alphas) - 1):
+        for j in (0, 5, len(betas) - 1):
+            assert C.ragc_cost_interp(g, alphas[i], betas[j]) == pytest.approx(t[i][j], rel=1e-12)
+    rng = random.Random(5)
+    for _ in range(200):
+        a, b = rng.uniform(0, 9000), rng.uniform(1, 1100)
+        assert C.ragc_cost_interp(g, a, b) == pytest.approx(KT.bilinear(alphas, betas, t, a, b), rel=1e-12)
+
+
+def test_trace_on_the_measured_grid_agrees_decision_by_decision():
+    g, alphas, betas, t = _measured()
+    to, tc = KT.KnowledgeTree(300, 600, alphas, betas, t), C.Tree(300, 600, g)
+    served = 0
+    for docs, dl, q in _zipf_trace(11, 600, 120):
+        try:
+            po = to.begin(docs, dl, q)
+        except KT.NoRoom:
+            with pytest.raises(B.RagcError):
+                tc.begin(docs, dl, q)
+            continue
+        pc = tc.begin(docs, dl, q)
+        _same_plan(po, pc)
+        for k in range(1, len(docs) + 1):
+            _same_node(to.find(docs[:k]), tc.find(docs[:k]))
+        to.end(po.request_id)
+        tc.end(pc.request_id)
+        served += 1
+    _same_stats(to, tc)
+    assert served > 500 and to.docs_hit > 0 and to.blocks_swapped_out > 0
+
+
+def test_policy_is_stable_under_the_measured_run_to_run_noise():
+    """PGDSF ranks nodes by Clock + AvgCost * Frequency / Size with costs from the table.  Perturb
+    every entry of the measured table by the run-to-run noise the profiler reported (independent
+    multiplicative errors, five draws) and replay one trace: the multiset of GPU evictions must stay
+    essentially the same and the hit rate must not move -- otherwise the measured differences that the
+    policy ranks on would be noise."""
+    g, alphas, betas, t = _measured()
+    noise = float(g.meta["run_to_run_rel_noise"])
+    trace = list(_zipf_trace(21, 1500, 200))
+
+    def replay(table):
+        tree = C.Tree(400, 2000, C.CostGrid(alphas, betas, table))
+        evicted = []
+        for docs, dl, q in trace:
+            p = tree.begin(docs, dl, q)
+            evicted.extend(p.evicted_gpu.tolist())
+            tree.end(p.request_id)
+        s = tree.stats()
+        return evicted, s.docs_hit / s.docs_requested
+
+    base_ev, base_hit = replay(np.asarray(t))
+    assert len(base_ev) > 200
+    rng = np.random.default_rng(3)
+    for _ in range(5):
+        ev, hit = replay(np.asarray(t) * (1.0 + rng.uniform(-noise, noise, np.asarray(t).shape)))
+        # one early swap of two near-equal priorities shifts every later position, so compare WHICH nodes
+        # were evicted how often, not the positions
+        common = sum((Counter(base_ev) & Counter(ev)).values()) / max(len(base_ev), len(ev))
+        assert abs(hit - base_hit) <= 0.005, (hit, base_hit)
+        assert common >= 0.85, common
+
+
+def test_two_requests_in_flight_that_share_a_new_document():
+    """The second request must not be handed the first one's unwritten blocks as cached prefix."""
+    to, tc = _pair(64, 64, lambda a, b: 2.0 * b)
+    ao, ac = to.begin([7, 8], [40, 24], 8), tc.begin([7, 8], [40, 24], 8)
+    _same_plan(ao, ac)
+    assert tc.peek([7], [40], 8) == to.peek([7], [40], 8) == (0, 48)
+    bo, bc = to.begin([7, 9], [40, 16], 8), tc.begin([7, 9], [40, 16], 8)
+    _same_plan(bo, bc)
+    assert (bc.matched_docs, bc.alpha, bc.beta) == (0, 0, 64)
+    assert not set(ac.block_table.tolist()) & set(bc.block_table.tolist())
+    assert tc.find([7, 9]) is None
+    for path in ([7], [7, 8]):
+        _same_node(to.find(path), tc.find(path))
+    assert tc.find([7]).num_computed == 2 and not tc.find([7]).computed
+    to.end(bo.request_id), tc.end(bc.request_id)
+    to.end(ao.request_id), tc.end(ac.request_id)
+    _same_stats(to, tc)
+    assert tc.find([7]).computed and tc.find([7, 8]).computed
+    co, cc = to.begin([7, 9], [40, 16], 8), tc.begin([7, 9], [40, 16], 8)
+    _same_plan(co, cc)
+    assert (cc.matched_docs, cc.alpha, cc.beta) == (1, 32, 32)
+    to.check_invariants()
