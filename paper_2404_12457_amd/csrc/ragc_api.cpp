@@ -254,7 +254,20 @@ int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, const HostMeta&
             plan->items.push_back({ragc::attn_bf16_item_cost(p, n, group, t),
                                    ragc::AttnItem{(uint32_t)r << 16 | (uint32_t)t, p, n, h.new_start[r]}});
     }
-    std::stable_sort(plan->items.begin(), plan->items.end(), [](const Bf16Item& x, const Bf16Item& y) { return x.cost > y.cost; });
+    // Order: requests by their most expensive row tile, longest first, and the row tiles of one
+    // request next to each other (longest first).  Long items start early, and the workgroups that
+    // run at the same time on an XCD walk the key tiles of the same few requests at about the same
+    // pace, so a tile fetched by one row tile is still in that XCD's L2 for the others.
+    std::vector<int32_t> req_cost(batch->num_reqs, 0);
+    for (const Bf16Item& it : plan->items) {
+        int32_t& c = req_cost[it.it.req_tile >> 16];
+        c = std::max(c, it.cost);
+    }
+    std::stable_sort(plan->items.begin(), plan->items.end(), [&](const Bf16Item& x, const Bf16Item& y) {
+        const uint32_t rx = x.it.req_tile >> 16, ry = y.it.req_tile >> 16;
+        if (rx != ry) return req_cost[rx] != req_cost[ry] ? req_cost[rx] > req_cost[ry] : rx < ry;
+        return x.cost > y.cost;
+    });
     const int64_t wgs = (int64_t)plan->items.size() * pool->kv_heads;
     const int64_t cus = cu_count();
     // Fewer work items than CUs: split each along its keys until every CU has one, keeping at

@@ -46,9 +46,9 @@ def H():
 @pytest.mark.parametrize("gpu_blocks,host_slots,prefetch", [(40, 64, True), (40, 10, False), (512, 16, True)])
 def test_trace_through_controller_and_kernels(H, gpu_blocks, host_slots, prefetch):
     rng = random.Random(gpu_blocks * 1000 + host_slots)
-    grid = C.CostGrid([0.0, 4096.0], [1.0, 4096.0], [[1.0, 40.0], [3.0, 90.0]])
+    grid = C.CostGrid.load(C.MEASURED_GRID)  # T(alpha, beta) as profiled with the attention kernel itself
     tree = C.Tree(gpu_blocks, host_slots, grid)
-    model = KT.KnowledgeTree(gpu_blocks, host_slots, [0.0, 4096.0], [1.0, 4096.0], [[1.0, 40.0], [3.0, 90.0]])
+    model = KT.KnowledgeTree(gpu_blocks, host_slots, grid.alpha.tolist(), grid.beta.tolist(), grid.t.tolist())
     cache = H.LayeredCache(LAYERS, gpu_blocks, host_slots, HKV, D)
     lens = {d: rng.choice([rng.randrange(3, 40), rng.randrange(40, 130), 16 * rng.randrange(1, 6)]) for d in range(14)}
     scale = 1.0 / np.sqrt(D)
