@@ -435,3 +435,76 @@ def test_many_work_items_take_several_launches(H):
     lens = [(16 + (i % 5) * 16, 3 + (i % 7)) for i in range(300)]
     w = W.make_small("bf16", 2, 1, 64, lens, seed=7003)
     _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+
+
+def test_host_copies_of_the_lengths_are_optional(H):
+    """Without h_prefix_len / h_new_len / h_new_start the library reads the device arrays back
+    (synchronously) and must launch exactly the same work."""
+    w = W.make_small("bf16", 8, 2, 128, [(100, 37), (64, 64), (0, 20), (1500, 9)], seed=8101)
+    dw = H.DeviceWorkload(w)
+    ref = H.to_host(dw.attn(B.RAGC_ATTN_APPEND_FUSED)).copy()
+    pool_ref = _bits(dw.pool_k).clone()
+    bare = H.DeviceWorkload(w)
+    batch = B.make_batch(w.num_reqs, w.table_stride, bare.d_prefix_len, bare.d_new_len, bare.d_new_start, bare.d_block_table,
+                         None, None, None, None)
+    torch.cuda.synchronize()
+    need = B.ragc_prefill_attn_workspace(bare.pool, batch, w.q_heads, B.RAGC_ATTN_APPEND_FUSED)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    B.ragc_prefill_attn(bare.pool, batch, bare.q, bare.k_new, bare.v_new, bare.out, w.q_heads, w.softmax_scale,
+                        B.RAGC_ATTN_APPEND_FUSED, ws, ws.numel(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.to_host(bare.out), ref) and torch.equal(_bits(bare.pool_k), pool_ref)
+    fresh = H.DeviceWorkload(w)
+    batch2 = B.make_batch(w.num_reqs, w.table_stride, fresh.d_prefix_len, fresh.d_new_len, fresh.d_new_start, fresh.d_block_table,
+                          None, None, None, None)
+    B.ragc_kv_append(fresh.pool, batch2, fresh.k_new, fresh.v_new, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(fresh.pool_k), pool_ref)
+
+
+def test_validation_mode_finds_what_the_kernels_cannot_check(H):
+    """ragc_batch_validate / RAGC_ATTN_VALIDATE: append targets shared by two requests or lying in
+    another request's prefix, device arrays that differ from their host copies, table entries out
+    of range when no host table is given.  Every case is refused before anything is launched."""
+    w = W.make_small("bf16", 8, 2, 128, [(40, 30), (64, 20), (0, 9)], seed=8201)
+    dw = H.DeviceWorkload(w)
+    assert B.ragc_batch_validate(dw.pool, dw.batch, True) == 0
+    dw.attn(B.RAGC_ATTN_APPEND_FUSED | B.RAGC_ATTN_VALIDATE)  # a sound batch passes and runs
+    torch.cuda.synchronize()
+    before = _bits(dw.pool_k).clone()
+    st = torch.cuda.current_stream().cuda_stream
+
+    def refused(table, d_table=None, host_table=True, flags=B.RAGC_ATTN_APPEND_FUSED | B.RAGC_ATTN_VALIDATE):
+        ht = np.ascontiguousarray(table, np.int32)
+        dt = torch.from_numpy(ht if d_table is None else np.ascontiguousarray(d_table, np.int32)).cuda()
+        batch = B.make_batch(w.num_reqs, w.table_stride, dw.d_prefix_len, dw.d_new_len, dw.d_new_start, dt,
+                             dw.h_prefix_len, dw.h_new_len, dw.h_new_start, ht if host_table else None)
+        torch.cuda.synchronize()
+        with pytest.raises(B.RagcError) as e:
+            B.ragc_prefill_attn(dw.pool, batch, dw.q, dw.k_new, dw.v_new, dw.out, w.q_heads, w.softmax_scale, flags,
+                                dw.workspace, dw.workspace_bytes, st)
+        assert e.value.code == B.RAGC_ERR_RANGE
+        with pytest.raises(B.RagcError):
+            B.ragc_batch_validate(dw.pool, batch, True)
+        return B.ragc_last_error()
+
+    good = w.block_table.copy()
+    # request 1's first new token goes to table entry 64 // 16 = 4; let request 0's second append block (entry 3) be the same block
+    alias = good.copy()
+    alias[0, 3] = good[1, 4]
+    assert "append targets must be exclusive" in refused(alias)
+    # request 0 appends into a block that request 1 reads as cached prefix
+    inprefix = good.copy()
+    inprefix[0, 3] = good[1, 0]
+    assert "read as cached prefix" in refused(inprefix)
+    # the device table is not the host table
+    other = good.copy()
+    other[2, 0] = (good[2, 0] + 1) % w.num_blocks
+    assert "differs from host copy" in refused(good, d_table=other)
+    # no host table: the device table is read back and range-checked
+    bad = good.copy()
+    bad[1, 2] = w.num_blocks + 5
+    assert "outside [0," in refused(bad, host_table=False)
+    # without the flag the same aliasing batch is the caller's responsibility: only the range check of the host table runs
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(dw.pool_k), before)  # none of the refused calls wrote anything
