@@ -229,7 +229,7 @@ GRID_BETAS = [1] + [x for k in range(1, 9) for x in (128 * k, 128 * k + 1)][:-1]
 GRID_BATCH = 8
 
 
-def measure_cost_grid(harness, W, B, torch, write_path=None):
+def measure_cost_grid(harness, W, B, torch, write_path=None, quick=False):
     """T(alpha, beta) of the paper's cost model (Sec. 5.1, Algorithm 1), measured with this kernel:
     the time of one layer's attention with the fused append for a batch of GRID_BATCH requests with
     alpha cached and beta non-cached tokens each, LLaMA2-7B head shape, divided by GRID_BATCH.  A
@@ -268,18 +268,18 @@ def measure_cost_grid(harness, W, B, torch, write_path=None):
         batch = B.make_batch(GRID_BATCH, per_req, dev[0], dev[1], dev[2], d_table, hp, hn, hs, h_table)
         ws, nb = harness.workspace_for(pool, batch, hq, B.RAGC_ATTN_APPEND_FUSED)
         call = lambda i: B.ragc_prefill_attn(pool, batch, q, kn, vn, out, hq, scale, B.RAGC_ATTN_APPEND_FUSED, ws, nb, st)
-        em = sorted(_time_steps(call, 40, 10 if seg == 0 else 0, torch)[1] for seg in range(3))[1]  # median of three segments
+        em = sorted(_time_steps(call, 12 if quick else 40, 10 if seg == 0 else 0, torch)[1] for seg in range(3))[1]  # median of three segments
         return em * 1e3 / GRID_BATCH  # microseconds per request
 
     runs = []
-    for rep in range(2):
+    for rep in range(1 if quick else 2):  # quick: one pass with short segments (the default benchmark run)
         rows = []
         for a in GRID_ALPHAS:
             rows.append([one(a, b) for b in GRID_BETAS])
             print(f"cost grid run {rep}: alpha {a} done", file=sys.stderr, flush=True)
         runs.append(np.asarray(rows))
-    t = 0.5 * (runs[0] + runs[1])
-    noise = float(np.max(np.abs(runs[0] - runs[1]) / t))
+    t = sum(runs) / len(runs)
+    noise = float(np.max(np.abs(runs[0] - runs[-1]) / t)) if len(runs) > 1 else None
     grid = ctl.CostGrid(GRID_ALPHAS, GRID_BETAS, t)
     check = []
     for a, b in probes:
@@ -513,7 +513,7 @@ def main():
         del d5
         torch.cuda.empty_cache()
         # the controller side: measured cost model, layer-ahead copies over per-layer pools, tree throughput
-        extras["cost_grid"] = measure_cost_grid(harness, W, B, torch)
+        extras["cost_grid"] = measure_cost_grid(harness, W, B, torch, quick=True)
         extras["decode"] = measure_decode(harness, W, B, torch)
         extras["layer_prefetch"] = measure_layer_prefetch(harness, B, torch)
         extras["controller"] = measure_controller()
