@@ -561,22 +561,33 @@ __global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, Attn
     __bf16* const outp = static_cast<__bf16*>(a.out);
     const int r = chunk * RPW + threadIdx.x / TPR;
     if (r < rows_here) {
-        float m = -INFINITY;
-        for (int c = 0; c < S; ++c) {
-            if (ntiles_all * c / S >= ntiles_all * (c + 1) / S) continue;  // that copy had no tiles and wrote nothing
-            m = fmaxf(m, part0[c * copy_stride + TM * D + r * 2]);
+        // one round trip: every copy's (max, sum) and O piece are requested before any is used
+        float mc[kAttnMaxSplits], lc[kAttnMaxSplits];
+        f32x4 oc[kAttnMaxSplits];
+#pragma unroll
+        for (int c = 0; c < kAttnMaxSplits; ++c) {
+            mc[c] = -INFINITY;  // a copy that does not exist, or had no tiles and wrote nothing, weighs 0
+            lc[c] = 0.f;
+            oc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (c < S && ntiles_all * c / S < ntiles_all * (c + 1) / S) {
+                const float* pc = part0 + c * copy_stride;
+                const float2 ml = *reinterpret_cast<const float2*>(pc + TM * D + r * 2);
+                mc[c] = ml.x;
+                lc[c] = ml.y;
+                oc[c] = *reinterpret_cast<const f32x4*>(pc + r * D + d4 * 4);
+            }
         }
+        float m = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < kAttnMaxSplits; ++c) m = fmaxf(m, mc[c]);
         float l = 0.f;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < S; ++c) {
-            if (ntiles_all * c / S >= ntiles_all * (c + 1) / S) continue;
-            const float* pc = part0 + c * copy_stride;
-            const float mc = pc[TM * D + r * 2], lc = pc[TM * D + r * 2 + 1];
-            const float wgt = mc == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc - m);  // a copy may hold no visible key of the row
-            const f32x4 o = *reinterpret_cast<const f32x4*>(pc + r * D + d4 * 4);
-            l += lc * wgt;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += o[e] * wgt;
+        for (int c = 0; c < kAttnMaxSplits; ++c) {
+            const float wgt = mc[c] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mc[c] - m);  // a copy may hold no visible key of the row
+            l += lc[c] * wgt;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += oc[c][e] * wgt;
         }
         const float inv = 1.f / l;
         const int row = row0 + r;

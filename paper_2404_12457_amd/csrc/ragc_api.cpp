@@ -271,19 +271,22 @@ int plan_bf16(const ragc_kv_pool* pool, const ragc_batch* batch, const HostMeta&
     const int64_t wgs = (int64_t)plan->items.size() * pool->kv_heads;
     const int64_t cus = cu_count();
     // Fewer work items than CUs: split each along its keys until every CU has one, keeping at
-    // least eight key tiles per copy of the longest item (a copy costs about as much as ten tiles
-    // before its first and after its last one).  ragc_debug_set_attn_plan overrides (tests).
+    // least three key tiles per copy of the longest item (measured on eight small shapes: with the
+    // one-round-trip merge pass, copies of three to four tiles are still worth their fixed cost).
+    // ragc_debug_set_attn_plan overrides (tests).
     int splits = 1;
     if (!(flags & RAGC_ATTN_NO_SPLIT) && wgs > 0) {
         splits = (int)std::min<int64_t>(cus / wgs, ragc::kAttnMaxSplits);
-        splits = std::min(splits, plan->items.front().cost / 8);
+        splits = std::min(splits, plan->items.front().cost / 3);
         if (const int force = g_force_splits.load(std::memory_order_relaxed); force > 0) splits = std::min(force, ragc::kAttnMaxSplits);
         if (splits < 1) splits = 1;
     }
     plan->splits = splits;
     // With at least two workgroups per CU two 4-wave workgroups share a CU; otherwise one 8-wave
-    // workgroup divides its key tiles between two wave groups.  ragc_debug_set_attn_plan overrides (tests).
-    plan->variant = wgs * splits >= 2 * cus ? ragc::kAttnVariantOneGroup : ragc::kAttnVariantTwoGroups;
+    // workgroup divides its key tiles between two wave groups -- unless the items are already split
+    // along their keys (measured: 4-wave workgroups are then as fast or faster, 23.8 against 26.3 us
+    // on four decode requests of 4096 keys).  ragc_debug_set_attn_plan overrides (tests).
+    plan->variant = (splits > 1 || wgs >= 2 * cus) ? ragc::kAttnVariantOneGroup : ragc::kAttnVariantTwoGroups;
     if (const int force = g_force_variant.load(std::memory_order_relaxed); force >= 0) plan->variant = force;
     plan->workspace = splits > 1 ? (int64_t)plan->items.size() * splits * pool->kv_heads * ragc::attn_partial_bytes(pool->head_dim) : 0;
     return 0;
