@@ -295,13 +295,18 @@ def measure_cost_grid(harness, W, B, torch, write_path=None, quick=False):
     return res
 
 
-def measure_decode(harness, W, B, torch):
+DECODE_SHAPES = (("R64_P1024_gqa32/8", 64, 1024, 32, 8), ("R128_P2048_gqa32/8", 128, 2048, 32, 8),
+                 ("R8_P1024_mha32", 8, 1024, 32, 32), ("R4_P4096_gqa64/8", 4, 4096, 64, 8))
+
+
+def measure_decode(harness, W, B, torch, only=None):
     """Decode steps (one new token per request) on the same pool and kernel: the K/V of every
     request is read once, so the figure of merit is K/V bytes per second against the HBM peak.
     The same data is read every step (warm in the last-level cache when it fits)."""
     out = {}
-    for name, R, P, hq, hkv in (("R64_P1024_gqa32/8", 64, 1024, 32, 8), ("R128_P2048_gqa32/8", 128, 2048, 32, 8),
-                                ("R8_P1024_mha32", 8, 1024, 32, 32), ("R4_P4096_gqa64/8", 4, 4096, 64, 8)):
+    for name, R, P, hq, hkv in DECODE_SHAPES:
+        if only is not None and name != only:
+            continue
         w = W.make_small("bf16", hq, hkv, 128, [(P, 1)] * R, seed=3, sigma=0.5)
         dw = harness.DeviceWorkload(w)
         _, em = _time_steps(lambda i: dw.attn(B.RAGC_ATTN_APPEND_FUSED), 30, 5, torch)
@@ -390,6 +395,8 @@ def main():
     ap.add_argument("--force-splits", type=int, default=0, help="debug: copies of every work item along the keys (0 = library's choice)")
     ap.add_argument("--write-cost-grid", metavar="PATH", default=None,
                     help="measure T(alpha, beta) and write it as a JSON file that ctl.CostGrid.load reads; nothing else runs")
+    ap.add_argument("--decode-only", metavar="SHAPE", default=None,
+                    help="time one decode shape only (%s) and print its figures: the run to put under rocprofv3" % ", ".join(n for n, *_ in DECODE_SHAPES))
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain 512 MiB device copy three times (scale for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -410,6 +417,9 @@ def main():
     if args.write_cost_grid:
         res = measure_cost_grid(harness, W, B, torch, write_path=args.write_cost_grid)
         print(json.dumps({k: res[k] for k in ("run_to_run_rel_noise", "max_rel_err", "off_grid")}))
+        return
+    if args.decode_only:
+        print(json.dumps(measure_decode(harness, W, B, torch, only=args.decode_only)))
         return
     if args.calibrate_copy:
         src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
