@@ -22,6 +22,9 @@
 // overlaps the other's MFMAs.  With many work items NG = 1 and two workgroups share
 // a CU instead.
 //
+// A launch whose work items all have at most 32 rows (decode steps) is compiled with DEC: the
+// first two waves of a group share those rows and take one 32-key half of every tile each.
+//
 // A batch with few work items is also split along the keys ACROSS workgroups: a work item
 // then appears S times in the list, each copy walks 1/S of the key tiles and leaves its
 // unnormalised O and its (max, sum) per row in the caller's workspace, and attn_bf16_merge_kernel
@@ -45,8 +48,14 @@ constexpr int TM = kAttnRowsPerItem;  // rows per work item
 
 // SPLIT: the list holds several copies of every item, each with a share of the key tiles (a
 // separate instantiation, so that the common unsplit kernel carries none of it).
-template <int D, int NG, int RING, bool SPLIT>
+template <int D, int NG, int RING, bool SPLIT, bool DEC>
 __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn_bf16_kernel(AttnLaunch a, AttnWorkList wl) {
+    // DEC: every work item of the launch has at most 32 rows (decode steps: one new token times the
+    // group's q heads).  The rows then all sit in wave 0's block and three waves of four would only
+    // copy; instead waves 0 and 1 of a group both take those 32 rows and one 32-key half of every
+    // tile each, with private softmax state merged at the end like the wave groups' -- half the
+    // MFMAs and half the softmax per wave and tile, which is what a step costs when nothing overlaps it.
+    constexpr int NSUB = DEC ? 1 : 2;   // 32-key halves of a tile per wave
     constexpr int CPR = D / 8;          // 16-byte chunks per K/V row
     constexpr int ROWB = D * 2;         // bytes per row
     constexpr int PLANEB = TN * ROWB;   // one tile of K (or V)
@@ -108,12 +117,13 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     const int nsteps = (ntiles - t_lo + NG - 1) / NG;  // group `grp` takes tile t_lo + step*NG + grp
 
     // ---- this lane's query row
-    const int wrow0 = row0 + wq * 32;
+    const int wrow0 = row0 + (DEC ? 0 : wq * 32);
+    const int ksub = DEC ? wq * 32 : 0;  // DEC: this wave's half of every tile (waves 2 and 3 only copy)
     const int my_row = min(wrow0 + l32, rows_total - 1);  // rows past the end repeat the last one
     const int my_tok = div_g(my_row);
     const int my_head = g * G + (my_row - my_tok * G);
     const int my_vis = P + my_tok + 1;  // keys [0, my_vis) are visible to this row
-    const bool wave_active = wrow0 < rows_total;
+    const bool wave_active = wrow0 < rows_total && (!DEC || wq < 2);
     const int wave_vis_min = P + div_g(wrow0) + 1;
     const int wave_vis_max = P + div_g(min(wrow0 + 31, rows_total - 1)) + 1;
 
@@ -232,7 +242,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     int koff[KSTEPS];
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
-        koff[ks] = grp_off + l32 * ROWB + (((2 * ks + hf) ^ swz<D>(l32)) << 4);
+        koff[ks] = grp_off + (ksub + l32) * ROWB + (((2 * ks + hf) ^ swz<D>(l32)) << 4);
         asm volatile("" : "+v"(koff[ks]));  // keep it one register: address = this + immediate
     }
     // V, A operand of O^T (transposing read): rows kk*16 + 8*h2 + 4*hf + (lane&15)/4 + {sub*32},
@@ -244,7 +254,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         for (int dt = 0; dt < DT; ++dt) {
             const int row = 8 * h2 + 4 * hf + ((lane & 15) >> 2);
             const int elem = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-            voff[h2][dt] = grp_off + row * ROWB + ((((elem >> 3)) ^ swz<D>(row)) << 4) + (elem & 7) * 2;
+            voff[h2][dt] = grp_off + (ksub + row) * ROWB + ((((elem >> 3)) ^ swz<D>(row)) << 4) + (elem & 7) * 2;
             asm volatile("" : "+v"(voff[h2][dt]));
         }
 
@@ -267,7 +277,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         if (step + RING - 1 < nsteps) prepare(step + RING - 1);
 
         const int tg = t_lo + step * NG + grp;
-        const int base = tg * TN;
+        const int base = tg * TN + ksub;  // first key this wave looks at
         if (!wave_active || tg >= ntiles || base >= wave_vis_max) {
             flush();
             return;
@@ -276,36 +286,36 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         lds_char* const vst = kst + PLANEB;
 
         // S^T = K Q^T
-        f32x16 sacc[2];
+        f32x16 sacc[NSUB];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
             for (int i = 0; i < 16; ++i) sacc[sub][i] = 0.f;
         // K operands are read two k-steps ahead of the MFMAs that consume them (LDS latency is
         // about four MFMAs long)
-        bf16x8 kbuf[3][2];
+        bf16x8 kbuf[3][NSUB];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+            for (int sub = 0; sub < NSUB; ++sub)
                 kbuf[ks][sub] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks]);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             if (ks + 2 < KSTEPS) {
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
+                for (int sub = 0; sub < NSUB; ++sub)
                     kbuf[(ks + 2) % 3][sub] = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kst + sub * 32 * ROWB + koff[ks + 2]);
             }
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+            for (int sub = 0; sub < NSUB; ++sub)
                 sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kbuf[ks % 3][sub], qreg[ks], sacc[sub], 0, 0, 0);
             if (ks < IPB && pend) emit(ks);  // two DMA instructions in the shadow of the MFMAs just issued
         }
         pend = 0;
         // causal frontier / end of sequence: only tiles that reach past the first row's horizon
-        if (base + TN > wave_vis_min) {
+        if (base + NSUB * 32 > wave_vis_min) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+            for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int kidx = base + sub * 32 + (i >> 2) * 8 + hf * 4 + (i & 3);
@@ -315,7 +325,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         // online softmax, one row per lane pair (lane, lane^32)
         float mx = sacc[0][0];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[sub][i]);
         mx = fmaxf(mx, other_half(mx));
@@ -337,9 +347,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
         // The row sum is taken over the bf16-rounded probabilities, the same weights the PV
         // product uses, so that the rounding of P cancels between numerator and denominator.
         float psum = 0.f;
-        bf16x8 pb[2][2];
+        bf16x8 pb[NSUB][2];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(sacc[sub][i] * c - m_sub);
@@ -353,7 +363,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 
         // O^T += V^T P^T ; V rows fetched with the transposing LDS read
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < NSUB; ++sub)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 lds_char* const vb = vst + (sub * 32 + kk * 16) * ROWB;
@@ -386,8 +396,9 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     }
 
     // ---- fused append (after the key loop: nothing waits for it, and the fresh rows are L2-hot
-    // because the loop has just read them as keys).  This work item owns the tokens whose first
-    // row (head 0 of the group) it holds; 16-byte chunks, four per thread in flight.
+    // because the loop has just read them as keys; requested up front, next to Q, the rows cost 1-4 %
+    // on the prefill configurations and gain 1-2 % on decode steps).  This work item owns the tokens
+    // whose first row (head 0 of the group) it holds; 16-byte chunks, four per thread in flight.
     if (a.fused_append && sidx == S - 1) {  // the last copy always has tiles
         const int tok_lo = div_g(row0 + G - 1);
         const int tok_hi = min(N - 1, div_g(row0 + TM - 1));
@@ -426,7 +437,49 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
 
     // ---- merge the wave groups through LDS (the DMA ring is idle now)
     constexpr int WSTRIDE = (DT * 16 + 4) * 64;  // floats per wave in the merge area: [DT*4 + 1 chunks][64 lanes][4]
-    if (NG > 1) {
+    if (DEC) {
+        // up to 2 * NG waves hold a state for the same 32 rows: wave (grp, wq < 2) is participant
+        // p = 2 * grp + wq; everyone but participant 0 leaves its state in area p, participant 0 adds
+        // them up one after the other and goes on alone
+        static_assert(2 * NG * WSTRIDE * 4 <= NSTAGE * STAGEB, "merge areas fit the ring");
+        typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+        const int part_id = 2 * grp + wq;
+        block_barrier();
+        if (wq < 2 && part_id != 0) {
+            lds_f32x4* const xw = reinterpret_cast<lds_f32x4*>(lds0 + part_id * (WSTRIDE * 4)) + lane;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 v = {oacc[dt][i4 * 4], oacc[dt][i4 * 4 + 1], oacc[dt][i4 * 4 + 2], oacc[dt][i4 * 4 + 3]};
+                    xw[(dt * 4 + i4) * 64] = v;
+                }
+            const f32x4 ml = {m_run, l_run, 0.f, 0.f};
+            xw[DT * 4 * 64] = ml;
+        }
+        block_barrier();
+        if (w != 0) return;
+#pragma unroll 1
+        for (int other = 1; other < 2 * NG; ++other) {
+            lds_f32x4* const xw = reinterpret_cast<lds_f32x4*>(lds0 + other * (WSTRIDE * 4)) + lane;
+            const f32x4 ml = xw[DT * 4 * 64];
+            const float m1 = ml[0], l1 = ml[1];
+            // a participant (or, with a key split, all of them) may have seen no visible key of a row: weight 0
+            const float m = fmaxf(m_run, m1);
+            const float s0f = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m);
+            const float s1f = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+            m_run = m;
+            l_run = l_run * s0f + l1 * s1f;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const f32x4 v = xw[(dt * 4 + i4) * 64];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) oacc[dt][i4 * 4 + e] = oacc[dt][i4 * 4 + e] * s0f + v[e] * s1f;
+                }
+        }
+    } else if (NG > 1) {
         typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
         lds_f32x4* const xw = reinterpret_cast<lds_f32x4*>(lds0 + wq * (WSTRIDE * 4)) + lane;
         block_barrier();
@@ -472,7 +525,7 @@ __global__ __launch_bounds__(256 * NG, (NG == 1 && RING == 2) ? 2 : 1) void attn
     if (!wave_active) return;
     constexpr int OROWB = ROWB + 16;
     static_assert(32 * OROWB <= WSTRIDE * 4, "output patch fits the merge area");
-    lds_char* const patch = lds0 + wq * (NG > 1 ? WSTRIDE * 4 : 32 * OROWB);
+    lds_char* const patch = lds0 + wq * (NG > 1 ? WSTRIDE * 4 : 32 * OROWB);  // DEC: wave 0 only, area 0 holds no state
     const float l_tot = l_run + other_half(l_run);
     if (SPLIT) {
         // ---- one of S copies of the item: leave O (unnormalised, fp32), max and sum of every row in the
@@ -600,12 +653,17 @@ __global__ __launch_bounds__(256) void attn_bf16_merge_kernel(AttnLaunch a, Attn
     }
 }
 
+template <int D, int NG, int RING, bool DEC>
+void launch_dec(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
+    if (wl.splits > 1)
+        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, true, DEC>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+    else
+        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, false, DEC>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+}
 template <int D, int NG, int RING>
 void launch_one(const AttnLaunch& a, const AttnWorkList& wl, hipStream_t s) {
-    if (wl.splits > 1)
-        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, true>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
-    else
-        hipLaunchKernelGGL((attn_bf16_kernel<D, NG, RING, false>), dim3(wl.n * a.b.kv_heads), dim3(256 * NG), 0, s, a, wl);
+    if (a.max_new * a.group <= 32) launch_dec<D, NG, RING, true>(a, wl, s);  // every item has at most 32 rows
+    else launch_dec<D, NG, RING, false>(a, wl, s);
 }
 
 }  // namespace

@@ -353,6 +353,30 @@ def test_key_split_across_workgroups_matches_oracle(H, variant, splits, force_pl
     assert np.max(np.abs(got_split - got_one)) <= 2e-3
 
 
+@pytest.mark.parametrize("variant,splits", [(0, 1), (1, 1), (0, 3), (1, 5), (None, None)])
+def test_decode_batches_take_the_two_waves_per_tile_mode(H, variant, splits, force_plan):
+    """A bf16 batch whose items all have at most 32 rows (decode steps, or a few new tokens times a
+    small group) runs in the mode where two waves of a group share the rows and halve every key
+    tile.  Ragged prefixes (empty, shorter than a half tile, across block and tile edges), every
+    group size that fits, both head dims, forced and chosen layouts, fused append checked bit for bit."""
+    force_plan(variant, splits)
+    cases = [
+        (8, 8, 128, [(0, 1), (1, 1), (15, 1), (16, 1), (31, 1), (32, 1), (33, 1), (63, 1), (64, 1), (65, 1), (200, 1), (1000, 1)], 1.0),
+        (32, 4, 128, [(5, 1), (100, 1), (777, 1), (2049, 1)], 1.0),      # 8 rows
+        (32, 1, 64, [(0, 1), (40, 1), (500, 1)], 4.0),                   # 32 rows, head_dim 64, sharper softmax
+        (8, 2, 128, [(3, 8), (90, 5), (130, 1), (0, 7)], 1.0),           # a few new tokens: 4 rows per token, causal inside the tile
+        (16, 16, 64, [(17, 30), (260, 32), (0, 2)], 1.0),                # MHA, up to 32 new tokens
+    ]
+    for i, (hq, hkv, d, lens, gain) in enumerate(cases):
+        w = W.make_small("bf16", hq, hkv, d, lens, seed=7300 + i, q_gain=gain)
+        assert max(n for _, n in lens) * (hq // hkv) <= 32
+        dw, _, _ = _check_all(H, w, B.RAGC_ATTN_APPEND_FUSED)
+        pk, pv = w.pool_image()
+        OP.append(pk, pv, w.block_table, w.prefix_len, w.new_len, w.new_start, w.k_new, w.v_new)
+        assert torch.equal(_bits(dw.pool_k), _bits(H.to_device(pk, "bf16")))
+        assert torch.equal(_bits(dw.pool_v), _bits(H.to_device(pv, "bf16")))
+
+
 def test_split_is_chosen_for_a_single_request_and_for_decode_steps(H):
     """No override: one request with a long cached prefix, and a small decode batch, are split
     (the workspace query says so) and match the oracle; a batch that fills the chip is not."""
