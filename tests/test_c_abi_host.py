@@ -135,6 +135,27 @@ def test_debug_plan_override_changes_the_workspace_and_rejects_bad_values(lib):
     assert B.ragc_prefill_attn_workspace(pool, one, 8) == auto
 
 
+def test_key_split_rule_as_seen_through_the_workspace_size(lib):
+    """S = min(CUs / workgroups, key tiles of the longest item / 3, 16), 256 CUs when no GPU is visible
+    (an MI355X has as many); the workspace is one partial result per (item, copy, kv head)."""
+    part = 128 * (128 + 2) * 4
+
+    def copies(p, n, hq, hkv, stride=1200):
+        b, keep = _batch(p=p, n=n, stride=stride)
+        items = sum(-(-(x * (hq // hkv)) // 128) for x in n)
+        ws = B.ragc_prefill_attn_workspace(_pool(num_blocks=4096, kv_heads=hkv), b, hq)
+        assert ws % (items * hkv * part) == 0
+        return ws // (items * hkv * part)  # 0: not split
+
+    assert copies((4096,) * 4, (1,) * 4, 64, 8) == 8       # 32 workgroups, 65 tiles: every CU gets one
+    assert copies((1024,), (100,), 32, 32) == 6            # 32 workgroups, 18 tiles: three tiles per copy
+    assert copies((2048,) * 2, (1,) * 2, 32, 8) == 11      # 16 workgroups, 33 tiles
+    assert copies((16384,), (1,), 32, 8) == 16             # capped
+    assert copies((1024,) * 8, (1,) * 8, 32, 32) == 0      # 256 workgroups already
+    assert copies((100,), (20,), 8, 8) == 0                # two tiles: nothing to split
+    assert copies((256,) * 8, (100,) * 8, 32, 32) == 0
+
+
 def test_size_limits_and_workspace_errors(lib):
     many, keep = _batch(p=(0,) * 65536, n=(1,) * 65536, stride=1)
     assert _attn_code(_pool(), many) == B.RAGC_ERR_SHAPE  # more requests than a work item can name
