@@ -433,6 +433,31 @@ def _check_with_append(H, w):
     return got, want
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_randomised_decode_batches_match_oracle(H, seed, force_plan):
+    """Random batches in which no request has more than 32 rows (the two-waves-per-tile mode): 1 to 40
+    requests, random group size and head dim, prefixes from empty to 5000 keys, one to 32/G new
+    tokens, random layout (4 or 8 waves, 1 to 16 key copies or the library's choice)."""
+    import random
+
+    rng = random.Random(9500 + seed)
+    hkv = rng.choice([1, 2, 4, 8])
+    group = rng.choice([1, 2, 4, 5, 8, 16, 32])
+    d = rng.choice([64, 128])
+    edge = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129]
+    lens = []
+    for _ in range(rng.randrange(1, 41)):
+        p = rng.choice([rng.choice(edge), rng.randrange(0, 700), rng.randrange(0, 5000)])
+        n = rng.choice([0, 1, 1, 1, rng.randrange(1, 32 // group + 1)])
+        lens.append((p, n))
+    if all(n == 0 for _, n in lens):
+        lens.append((rng.randrange(0, 300), 1))
+    force_plan(rng.randrange(2), rng.choice([1, 2, 3, 5, 8, 16]) if rng.random() < 0.5 else 0)
+    w = W.make_small("bf16", hkv * group, hkv, d, lens, seed=9600 + seed, q_gain=rng.choice([1.0, 4.0]))
+    assert max(n for _, n in lens) * group <= 32
+    _check_with_append(H, w)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_randomised_shapes_match_oracle(H, seed, force_plan):
     """Unit-variance values and sharp softmaxes (q gain up to 8): output against the oracle at
